@@ -1,0 +1,169 @@
+/*
+ * owq.h - C ABI of the OWQ mixed-precision linear layer for AMD MI355X (gfx950).
+ *
+ * The layer is the one the OWQ paper (arxiv 2306.02272) stores and runs at
+ * inference time: a full-size matrix of 3- or 4-bit codes whose weak-column
+ * positions are zero-filled, a step size and zero point per output channel or
+ * per group of input columns, k "weak" input columns kept in fp16, and one
+ * integer index per weak column (section "Outlier-Aware Weight Quantization",
+ * storage paragraph; appendix B.2, latency-favoured format).  One call
+ * evaluates, for every row n of a batch of fp16 activations,
+ *
+ *     y[n, i] = sum_{j not weak} s[i, g(j)] * (q[i, j] - z[i, g(j)]) * x[n, j]
+ *             + sum_{t < k}      Ww[i, t] * x[n, weak_idx[t]]
+ *
+ * which is the dequantised dense matrix-vector product plus the product of
+ * the fp16 weak columns with the activations gathered at their indices
+ * (section "Acceleration on Real Device").  Shapes follow Eq. (3): W is
+ * d_out x d_in; the activations are passed transposed, one row per token.
+ *
+ * All functions return a status code; none throws, aborts or prints.
+ * Pointers are marked HOST or DEVICE.  Streams are hipStream_t passed as
+ * void* (NULL = the default stream).
+ */
+#ifndef OWQ_H
+#define OWQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct owq_layer_s *owq_handle_t; /* opaque; owned by the library until owq_free_layer */
+
+typedef enum {
+  OWQ_OK = 0,
+  OWQ_ERR_NULL = 1,       /* a required pointer is NULL */
+  OWQ_ERR_SHAPE = 2,      /* d_out < 1, d_in < 1 or a size does not fit 32-bit indexing */
+  OWQ_ERR_BITS = 3,       /* bits is neither 3 nor 4 */
+  OWQ_ERR_GROUP = 4,      /* group_size is neither 0 nor a positive multiple of 128 */
+  OWQ_ERR_CODE_RANGE = 5, /* a code at a non-weak column is >= 2^bits */
+  OWQ_ERR_INDEX = 6,      /* k out of [0, d_in], or weak_idx not strictly ascending in [0, d_in) */
+  OWQ_ERR_BUFFER = 7,     /* a buffer is too small or misaligned */
+  OWQ_ERR_BATCH = 8,      /* batch < 0 or above OWQ_MAX_BATCH */
+  OWQ_ERR_HANDLE = 9,     /* not a live handle */
+  OWQ_ERR_HIP = 10,       /* a HIP call failed; see owq_layer_info_t.last_hip_error */
+  OWQ_ERR_UNSUPPORTED = 11 /* the layer needs more on-chip memory than one workgroup may use */
+} owq_status_t;
+
+#define OWQ_MAX_BATCH 65535
+#define OWQ_FORMAT_VERSION 1
+
+/*
+ * Plain description of a layer.  Every pointer is HOST memory, borrowed for the
+ * duration of the call only.
+ *   codes     [d_out][d_in], one code per byte, row-major.  Values at weak
+ *             columns are ignored and stored as 0 (the zero-filled positions).
+ *   scale     fp16 bit patterns, [d_out][G]; G = 1 if group_size == 0, else
+ *             ceil(d_in / group_size).  Groups are runs of group_size
+ *             consecutive input columns of a row.
+ *   zero      fp16 bit patterns, [d_out][G] (any finite fp16 value).
+ *   weak_idx  [k], strictly ascending, each in [0, d_in).  May be NULL if k == 0.
+ *   weak_w    fp16 bit patterns, [d_out][k] row-major; column t belongs to input
+ *             column weak_idx[t].  May be NULL if k == 0.
+ */
+typedef struct {
+  int32_t d_out, d_in;
+  int32_t bits;       /* 3 or 4 */
+  int32_t group_size; /* 0 = per output channel; else a multiple of 128 */
+  int32_t k;
+  const uint8_t *codes;
+  const uint16_t *scale;
+  const uint16_t *zero;
+  const int32_t *weak_idx;
+  const uint16_t *weak_w;
+} owq_layer_desc_t;
+
+/*
+ * Geometry of the packed blob (format version 1) and the launch shape in use.
+ * A block is 128 consecutive input columns of one row; a tile is r rows by cw
+ * blocks; the blob is four 256-byte-aligned sections (codes, scale/zero pairs,
+ * weak weights, weak indices).
+ */
+typedef struct {
+  int32_t format_version;
+  int32_t d_out, d_in, bits, group_size, k;
+  int32_t nblk, cw, r, nact, nslab, n_rt, d_out_pad, chunks, n_groups, kp;
+  uint64_t off_codes, off_sz, off_weak_w, off_weak_idx, total_bytes;
+  /* launch shape of the batch <= 16 path (filled for handles only) */
+  int32_t row_tiles_per_wg, row_splits, waves_per_wg, prefetch_depth;
+  int32_t workgroups, lds_bytes;
+  int32_t last_hip_error;
+  int32_t reserved;
+} owq_layer_info_t;
+
+/* Geometry for a description; needs no GPU.  Only the shape fields of desc are read. */
+owq_status_t owq_geometry(const owq_layer_desc_t *desc, owq_layer_info_t *info);
+
+/* Bytes of DEVICE (or host) memory the packed blob of this layer needs. */
+owq_status_t owq_packed_bytes(const owq_layer_desc_t *desc, size_t *bytes);
+
+/*
+ * Validate desc and write the packed blob into HOST memory host_buf (at least
+ * owq_packed_bytes bytes; every byte of the blob is written).  Needs no GPU.
+ */
+owq_status_t owq_pack_host(const owq_layer_desc_t *desc, void *host_buf, size_t bytes);
+
+/*
+ * Inverse of the code packing: read the codes section of a HOST blob laid out as
+ * info describes and write codes [d_out][d_in], one per byte, to HOST memory.
+ */
+owq_status_t owq_unpack_codes(const void *host_packed, const owq_layer_info_t *info, uint8_t *codes);
+
+/*
+ * Validate, pack on the host and upload into DEVICE memory dev_buf (256-byte
+ * aligned, at least owq_packed_bytes bytes, owned by the caller, who keeps it
+ * alive and unmodified until owq_free_layer).  The copy is enqueued on stream
+ * and the call returns after it has completed.  On success *out is a new handle.
+ */
+owq_status_t owq_pack_layer(const owq_layer_desc_t *desc, void *dev_buf, size_t dev_bytes,
+                            void *stream, owq_handle_t *out);
+
+/*
+ * Make a handle over a blob that already sits in DEVICE memory dev_buf in packed
+ * form (written earlier by owq_pack_host / owq_pack_layer / owq_export_packed for
+ * a layer of the same shape, e.g. read back from a file or copied on the device).
+ * Only the shape fields of desc are read; the blob's contents are not checked.
+ * dev_buf: 256-byte aligned, at least owq_packed_bytes bytes, owned by the caller.
+ */
+owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t dev_bytes,
+                             owq_handle_t *out);
+
+/*
+ * y = layer(x) for a batch of activations.
+ *   x  DEVICE, fp16, [batch][d_in] row-major
+ *   y  DEVICE, fp16, [batch][d_out] row-major, written in full; must not overlap x
+ * Products are accumulated in fp32 and rounded once to fp16 (nearest even).
+ * The work is enqueued on stream; the call does not wait, allocate or copy.
+ * batch == 0 is a no-op.  The device of dev_buf must be current.
+ * Handles are immutable: concurrent calls on different streams are allowed.
+ */
+owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream);
+
+/* Release the handle (the host-side record only; dev_buf stays with the caller). */
+owq_status_t owq_free_layer(owq_handle_t h);
+
+/* Geometry, launch shape and last HIP error of a handle. */
+owq_status_t owq_layer_info(owq_handle_t h, owq_layer_info_t *info);
+
+/* Copy the packed blob back from the device into HOST memory; waits for the copy. */
+owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes);
+
+/*
+ * Tuning hook for benchmarks: override the launch shape of the batch <= 16 path.
+ * row_tiles_per_wg >= 1; row_splits divides row_tiles_per_wg; waves_per_wg in
+ * [1, 8] divides nslab * row_splits; prefetch_depth in {1, 2, 4}.  A value of 0
+ * keeps the current setting.  Rejected shapes leave the handle unchanged.
+ * Not thread-safe against concurrent owq_linear on the same handle.
+ */
+owq_status_t owq_set_launch(owq_handle_t h, int32_t row_tiles_per_wg, int32_t row_splits,
+                            int32_t waves_per_wg, int32_t prefetch_depth);
+
+const char *owq_status_str(owq_status_t s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OWQ_H */

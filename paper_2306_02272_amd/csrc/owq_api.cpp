@@ -1,0 +1,214 @@
+// extern "C" entry points: argument checks, handles, upload; see include/owq.h.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "owq_internal.h"
+
+using namespace owq;
+
+static bool live(owq_handle_t h) { return h && h->magic == kMagic; }
+
+extern "C" {
+
+owq_status_t owq_geometry(const owq_layer_desc_t *desc, owq_layer_info_t *info) {
+  if (!desc || !info) return OWQ_ERR_NULL;
+  return compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, info);
+}
+
+owq_status_t owq_packed_bytes(const owq_layer_desc_t *desc, size_t *bytes) {
+  if (!desc || !bytes) return OWQ_ERR_NULL;
+  owq_layer_info_t g;
+  owq_status_t st = compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  if (st != OWQ_OK) return st;
+  *bytes = (size_t)g.total_bytes;
+  return OWQ_OK;
+}
+
+owq_status_t owq_pack_host(const owq_layer_desc_t *desc, void *host_buf, size_t bytes) {
+  if (!desc || !host_buf) return OWQ_ERR_NULL;
+  owq_status_t st = validate_desc(desc);
+  if (st != OWQ_OK) return st;
+  owq_layer_info_t g;
+  compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  if (bytes < g.total_bytes) return OWQ_ERR_BUFFER;
+  pack_blob(desc, g, static_cast<uint8_t *>(host_buf));
+  return OWQ_OK;
+}
+
+owq_status_t owq_unpack_codes(const void *host_packed, const owq_layer_info_t *info, uint8_t *codes) {
+  if (!host_packed || !info || !codes) return OWQ_ERR_NULL;
+  owq_layer_info_t g;
+  owq_status_t st = compute_geometry(info->d_out, info->d_in, info->bits, info->group_size, info->k, &g);
+  if (st != OWQ_OK) return st;
+  const uint32_t *dwords = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(host_packed) + g.off_codes);
+  for (int32_t row = 0; row < g.d_out; ++row) {
+    const int32_t rt = row / g.r, rloc = row % g.r;
+    for (int32_t j = 0; j < g.d_in; ++j) {
+      const int32_t blk = j / kBlockCols, cin = j % kBlockCols;
+      const int64_t tile = (int64_t)rt * g.nslab + blk / g.cw;
+      const int32_t lane = rloc * g.cw + blk % g.cw;
+      int v, bit;          // dword of the lane, bit inside its 16-bit half
+      uint32_t code = 0;
+      const int half = cin & 1;
+      if (g.bits == 3) {
+        const int u = cin / 32, t = (cin % 32) / 2;
+        for (int b = 0; b < 3; ++b) {
+          const int sb = 3 * t + b;
+          v = 3 * u + sb / 16;
+          bit = sb % 16 + 16 * half;
+          const int64_t unit = (tile * g.chunks + v / 4) * g.nact + lane;
+          code |= ((dwords[unit * 4 + (v & 3)] >> bit) & 1u) << b;
+        }
+      } else {
+        v = cin / 8;
+        bit = 4 * ((cin % 8) / 2) + 16 * half;
+        const int64_t unit = (tile * g.chunks + v / 4) * g.nact + lane;
+        code = (dwords[unit * 4 + (v & 3)] >> bit) & 15u;
+      }
+      codes[(int64_t)row * g.d_in + j] = (uint8_t)code;
+    }
+  }
+  return OWQ_OK;
+}
+
+static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_handle_t *out) {
+  int32_t lds_limit = 0;
+  if (device_lds_limit(&lds_limit) != 0) return OWQ_ERR_HIP;
+  LaunchShape shape = default_shape(g, lds_limit);
+  if (shape.rtw < 1) return OWQ_ERR_UNSUPPORTED;
+  if (prepare_kernels(lds_limit) != 0) return OWQ_ERR_HIP;
+  owq_layer_s *h = new (std::nothrow) owq_layer_s;
+  if (!h) return OWQ_ERR_BUFFER;
+  h->magic = kMagic;
+  h->info = g;
+  h->shape = shape;
+  h->dev_buf = dev_buf;
+  h->lds_limit = lds_limit;
+  const uint8_t *base = static_cast<const uint8_t *>(dev_buf);
+  h->dev.codes = base + g.off_codes;
+  h->dev.sz = base + g.off_sz;
+  h->dev.weak_w = base + g.off_weak_w;
+  h->dev.weak_idx = base + g.off_weak_idx;
+  h->info.last_hip_error = 0;
+  *out = h;
+  return OWQ_OK;
+}
+
+owq_status_t owq_pack_layer(const owq_layer_desc_t *desc, void *dev_buf, size_t dev_bytes,
+                            void *stream, owq_handle_t *out) {
+  if (!desc || !dev_buf || !out) return OWQ_ERR_NULL;
+  *out = nullptr;
+  owq_status_t st = validate_desc(desc);
+  if (st != OWQ_OK) return st;
+  owq_layer_info_t g;
+  compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  if (dev_bytes < g.total_bytes) return OWQ_ERR_BUFFER;
+  if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign != 0) return OWQ_ERR_BUFFER;
+
+  uint8_t *host = nullptr;
+  if (hipHostMalloc(reinterpret_cast<void **>(&host), g.total_bytes, hipHostMallocDefault) != hipSuccess)
+    return OWQ_ERR_HIP;
+  pack_blob(desc, g, host);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(dev_buf, host, g.total_bytes, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipHostFree(host);
+  if (e != hipSuccess) return OWQ_ERR_HIP;
+  return make_handle(g, dev_buf, out);
+}
+
+owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t dev_bytes,
+                             owq_handle_t *out) {
+  if (!desc || !dev_buf || !out) return OWQ_ERR_NULL;
+  *out = nullptr;
+  owq_layer_info_t g;
+  owq_status_t st = compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  if (st != OWQ_OK) return st;
+  if (dev_bytes < g.total_bytes) return OWQ_ERR_BUFFER;
+  if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign != 0) return OWQ_ERR_BUFFER;
+  return make_handle(g, dev_buf, out);
+}
+
+owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (batch < 0 || batch > OWQ_MAX_BATCH) return OWQ_ERR_BATCH;
+  if (batch == 0) return OWQ_OK;
+  if (!x || !y) return OWQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(x) % 2 != 0 || reinterpret_cast<uintptr_t>(y) % 2 != 0) return OWQ_ERR_BUFFER;
+  const int herr = launch_gemv(h->info, h->shape, h->dev, x, y, batch, stream);
+  if (herr != 0) {
+    h->info.last_hip_error = herr;
+    return OWQ_ERR_HIP;
+  }
+  return OWQ_OK;
+}
+
+owq_status_t owq_free_layer(owq_handle_t h) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  h->magic = 0;
+  delete h;
+  return OWQ_OK;
+}
+
+owq_status_t owq_layer_info(owq_handle_t h, owq_layer_info_t *info) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (!info) return OWQ_ERR_NULL;
+  *info = h->info;
+  info->row_tiles_per_wg = h->shape.rtw;
+  info->row_splits = h->shape.rsplit;
+  info->waves_per_wg = h->shape.waves;
+  info->prefetch_depth = h->shape.depth;
+  info->workgroups = h->shape.nwg;
+  info->lds_bytes = h->shape.lds_bytes;
+  return OWQ_OK;
+}
+
+owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (!host_buf) return OWQ_ERR_NULL;
+  if (bytes < h->info.total_bytes) return OWQ_ERR_BUFFER;
+  hipError_t e = hipMemcpy(host_buf, h->dev_buf, h->info.total_bytes, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) {
+    h->info.last_hip_error = (int)e;
+    return OWQ_ERR_HIP;
+  }
+  return OWQ_OK;
+}
+
+owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t waves, int32_t depth) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  LaunchShape s = h->shape;
+  if (rtw) s.rtw = rtw;
+  if (rsplit) s.rsplit = rsplit;
+  if (waves) s.waves = waves;
+  if (depth) s.depth = depth;
+  if (s.rtw > h->info.n_rt) s.rtw = h->info.n_rt;
+  if (!shape_is_valid(h->info, s)) return OWQ_ERR_SHAPE;
+  s.lds_bytes = lds_bytes_for(h->info, s.rtw, &s.xpitch);
+  if (s.lds_bytes > h->lds_limit) return OWQ_ERR_UNSUPPORTED;
+  s.nwg = (h->info.n_rt + s.rtw - 1) / s.rtw;
+  h->shape = s;
+  return OWQ_OK;
+}
+
+const char *owq_status_str(owq_status_t s) {
+  switch (s) {
+    case OWQ_OK: return "ok";
+    case OWQ_ERR_NULL: return "null pointer";
+    case OWQ_ERR_SHAPE: return "bad shape";
+    case OWQ_ERR_BITS: return "bits must be 3 or 4";
+    case OWQ_ERR_GROUP: return "group_size must be 0 or a multiple of 128";
+    case OWQ_ERR_CODE_RANGE: return "code out of range";
+    case OWQ_ERR_INDEX: return "bad weak index list";
+    case OWQ_ERR_BUFFER: return "buffer too small or misaligned";
+    case OWQ_ERR_BATCH: return "bad batch";
+    case OWQ_ERR_HANDLE: return "not a live handle";
+    case OWQ_ERR_HIP: return "HIP call failed";
+    case OWQ_ERR_UNSUPPORTED: return "layer too large for one workgroup's on-chip memory";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

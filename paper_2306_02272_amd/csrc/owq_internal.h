@@ -1,0 +1,58 @@
+// Internal declarations shared by the host packer, the handle code and the kernels' launcher.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "owq.h"
+
+namespace owq {
+
+constexpr int kBlockCols = 128;   // input columns per block (one lane's unit of work)
+constexpr int kAlign = 256;       // section alignment inside the blob
+constexpr uint32_t kMagic = 0x4f575131u;  // "OWQ1"
+
+// Shape checks + geometry of the packed blob.  Fills every geometry field of info.
+owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t group_size,
+                              int32_t k, owq_layer_info_t *info);
+
+// Full validation of a description (pointers, code range, index order).
+owq_status_t validate_desc(const owq_layer_desc_t *desc);
+
+// Host packer: writes info->total_bytes bytes.
+void pack_blob(const owq_layer_desc_t *desc, const owq_layer_info_t &info, uint8_t *out);
+
+// Launch shape of the GEMV path.
+struct LaunchShape {
+  int32_t rtw;      // row tiles per workgroup
+  int32_t rsplit;   // row splits (waves sharing a slab take interleaved row tiles)
+  int32_t waves;    // waves per workgroup
+  int32_t depth;    // tiles in flight per wave
+  int32_t nwg;      // workgroups per batch row
+  int32_t lds_bytes;
+  int32_t xpitch;   // pitch (in 16-byte units) of the staged activations
+};
+
+bool shape_is_valid(const owq_layer_info_t &g, const LaunchShape &s);
+int32_t lds_bytes_for(const owq_layer_info_t &g, int32_t rtw, int32_t *xpitch);
+LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit);
+
+// Device-side launch (defined in owq_kernels.hip).  Returns a hipError_t as int.
+struct DeviceLayer {
+  const void *codes, *sz, *weak_w, *weak_idx;
+};
+int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev,
+                const void *x, void *y, int32_t batch, void *stream);
+int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when needed
+int device_lds_limit(int32_t *bytes);
+
+}  // namespace owq
+
+struct owq_layer_s {
+  uint32_t magic;
+  owq_layer_info_t info;
+  owq::LaunchShape shape;
+  owq::DeviceLayer dev;
+  void *dev_buf;
+  int32_t lds_limit;
+};

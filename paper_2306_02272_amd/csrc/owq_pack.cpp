@@ -1,0 +1,214 @@
+// Host side of the packed format: geometry, validation, packing and unpacking.
+//
+// What is stored follows the storage paragraph of the paper's "Outlier-Aware
+// Weight Quantization" section and appendix B.2 (latency-favoured format): the
+// full-size low-bit matrix with zero-filled weak positions, per-channel or
+// per-group step size and zero point, fp16 weak columns and their indices.
+// The bit layout is this library's own (the paper gives none); it is chosen so
+// that a lane of the GEMV kernel fetches one block of 128 codes with three or
+// four coalesced 16-byte loads and extracts pairs of codes straight into the
+// mantissas of two packed fp16 numbers.
+#include <cstring>
+
+#include "owq_internal.h"
+
+namespace owq {
+
+static inline uint64_t align_up(uint64_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t group_size,
+                              int32_t k, owq_layer_info_t *g) {
+  if (d_out < 1 || d_in < 1) return OWQ_ERR_SHAPE;
+  if (bits != 3 && bits != 4) return OWQ_ERR_BITS;
+  if (group_size < 0 || (group_size != 0 && group_size % kBlockCols != 0)) return OWQ_ERR_GROUP;
+  if (k < 0 || k > d_in) return OWQ_ERR_INDEX;
+  std::memset(g, 0, sizeof(*g));
+  g->format_version = OWQ_FORMAT_VERSION;
+  g->d_out = d_out; g->d_in = d_in; g->bits = bits; g->group_size = group_size; g->k = k;
+  g->nblk = (d_in + kBlockCols - 1) / kBlockCols;
+  // Tile width: as many blocks of a row side by side as the wave can hold while
+  // keeping at least 60 of its 64 lanes busy.
+  int cw = 1;
+  for (int c = 1; c <= 64 && c <= g->nblk; ++c)
+    if (g->nblk % c == 0 && (64 / c) * c >= 60) cw = c;
+  g->cw = cw;
+  g->r = 64 / cw;
+  g->nact = g->r * cw;
+  g->nslab = g->nblk / cw;
+  g->n_rt = (d_out + g->r - 1) / g->r;
+  g->d_out_pad = g->n_rt * g->r;
+  g->chunks = bits == 3 ? 3 : 4;
+  g->n_groups = group_size == 0 ? 1 : (d_in + group_size - 1) / group_size;
+  g->kp = (k + 7) / 8 * 8;
+  const uint64_t codes_bytes = (uint64_t)g->d_out_pad * g->nblk * g->chunks * 16;
+  g->off_codes = 0;
+  g->off_sz = align_up(codes_bytes);
+  g->off_weak_w = align_up(g->off_sz + (uint64_t)g->d_out_pad * g->n_groups * 4);
+  g->off_weak_idx = align_up(g->off_weak_w + (uint64_t)g->d_out_pad * g->kp * 2);
+  g->total_bytes = align_up(g->off_weak_idx + (uint64_t)g->kp * 4);
+  // The kernels index 16-byte units and rows with 32-bit integers.
+  if (g->total_bytes / 16 >= (1ull << 31)) return OWQ_ERR_SHAPE;
+  if ((uint64_t)g->d_out_pad * (uint64_t)(g->n_groups > g->kp ? g->n_groups : g->kp) >= (1ull << 31))
+    return OWQ_ERR_SHAPE;
+  return OWQ_OK;
+}
+
+owq_status_t validate_desc(const owq_layer_desc_t *d) {
+  if (!d) return OWQ_ERR_NULL;
+  owq_layer_info_t g;
+  owq_status_t st = compute_geometry(d->d_out, d->d_in, d->bits, d->group_size, d->k, &g);
+  if (st != OWQ_OK) return st;
+  if (!d->codes || !d->scale || !d->zero) return OWQ_ERR_NULL;
+  if (d->k > 0 && (!d->weak_idx || !d->weak_w)) return OWQ_ERR_NULL;
+  int32_t prev = -1;
+  for (int32_t t = 0; t < d->k; ++t) {
+    const int32_t j = d->weak_idx[t];
+    if (j <= prev || j >= d->d_in) return OWQ_ERR_INDEX;
+    prev = j;
+  }
+  std::vector<uint8_t> weak(d->d_in, 0);
+  for (int32_t t = 0; t < d->k; ++t) weak[d->weak_idx[t]] = 1;
+  const uint8_t limit = (uint8_t)(1u << d->bits);
+  for (int64_t i = 0; i < d->d_out; ++i) {
+    const uint8_t *row = d->codes + i * (int64_t)d->d_in;
+    uint8_t bad = 0;
+    for (int32_t j = 0; j < d->d_in; ++j) bad |= (uint8_t)((row[j] >= limit) & !weak[j]);
+    if (bad) return OWQ_ERR_CODE_RANGE;
+  }
+  return OWQ_OK;
+}
+
+// Codes of one block (128 columns of one row, weak and out-of-range columns
+// already forced to 0) -> the 12 or 16 dwords its lane owns.
+static void block_to_dwords(const uint8_t *q, int bits, uint32_t *dw) {
+  if (bits == 3) {
+    for (int u = 0; u < 4; ++u) {          // 32 codes -> two 48-bit streams -> 3 dwords
+      uint64_t even = 0, odd = 0;
+      for (int t = 0; t < 16; ++t) {
+        even |= (uint64_t)q[32 * u + 2 * t] << (3 * t);
+        odd |= (uint64_t)q[32 * u + 2 * t + 1] << (3 * t);
+      }
+      for (int w = 0; w < 3; ++w)
+        dw[3 * u + w] = (uint32_t)((even >> (16 * w)) & 0xffffu) |
+                        ((uint32_t)((odd >> (16 * w)) & 0xffffu) << 16);
+    }
+  } else {
+    for (int v = 0; v < 16; ++v) {
+      uint32_t even = 0, odd = 0;
+      for (int t = 0; t < 4; ++t) {
+        even |= (uint32_t)q[8 * v + 2 * t] << (4 * t);
+        odd |= (uint32_t)q[8 * v + 2 * t + 1] << (4 * t);
+      }
+      dw[v] = even | (odd << 16);
+    }
+  }
+}
+
+void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *out) {
+  std::memset(out, 0, g.total_bytes);
+  std::vector<uint8_t> weak(d->d_in, 0);
+  for (int32_t t = 0; t < d->k; ++t) weak[d->weak_idx[t]] = 1;
+
+  uint32_t *codes = reinterpret_cast<uint32_t *>(out + g.off_codes);
+  uint8_t q[kBlockCols];
+  uint32_t dw[16];
+  const int ndw = g.chunks * 4;
+  for (int32_t row = 0; row < g.d_out; ++row) {
+    const int32_t rt = row / g.r, rloc = row % g.r;
+    const uint8_t *src = d->codes + (int64_t)row * d->d_in;
+    for (int32_t blk = 0; blk < g.nblk; ++blk) {
+      const int32_t s = blk / g.cw, bloc = blk % g.cw;
+      for (int c = 0; c < kBlockCols; ++c) {
+        const int32_t j = blk * kBlockCols + c;
+        q[c] = (j < d->d_in && !weak[j]) ? src[j] : 0;
+      }
+      block_to_dwords(q, g.bits, dw);
+      const int64_t tile = (int64_t)rt * g.nslab + s;
+      const int32_t lane = rloc * g.cw + bloc;
+      for (int v = 0; v < ndw; ++v) {
+        const int64_t unit = (tile * g.chunks + v / 4) * g.nact + lane;   // 16-byte unit
+        codes[unit * 4 + (v & 3)] = dw[v];
+      }
+    }
+  }
+
+  uint32_t *sz = reinterpret_cast<uint32_t *>(out + g.off_sz);
+  for (int64_t i = 0; i < (int64_t)g.d_out * g.n_groups; ++i)
+    sz[i] = (uint32_t)d->scale[i] | ((uint32_t)d->zero[i] << 16);
+
+  uint16_t *ww = reinterpret_cast<uint16_t *>(out + g.off_weak_w);
+  for (int64_t i = 0; i < g.d_out; ++i)
+    for (int32_t t = 0; t < g.k; ++t) ww[i * g.kp + t] = d->weak_w[i * (int64_t)g.k + t];
+
+  int32_t *ix = reinterpret_cast<int32_t *>(out + g.off_weak_idx);
+  for (int32_t t = 0; t < g.kp; ++t) ix[t] = t < g.k ? d->weak_idx[t] : -1;
+}
+
+// ---------------------------------------------------------------------------
+// launch shape
+// ---------------------------------------------------------------------------
+
+int32_t lds_bytes_for(const owq_layer_info_t &g, int32_t rtw, int32_t *xpitch) {
+  const int32_t pitch = (g.nblk & 1) ? g.nblk : g.nblk + 1;   // odd pitch: conflict-free transposed writes
+  if (xpitch) *xpitch = pitch;
+  const int64_t xs = (int64_t)16 * pitch * 16;
+  const int64_t xw = ((int64_t)g.kp * 2 + 15) / 16 * 16;
+  const int64_t part = (int64_t)rtw * g.r * g.nblk * 4;
+  const int64_t total = xs + xw + part;
+  return total > 0x7fffffff ? 0x7fffffff : (int32_t)total;
+}
+
+bool shape_is_valid(const owq_layer_info_t &g, const LaunchShape &s) {
+  if (s.rtw < 1 || s.rsplit < 1 || s.waves < 1 || s.waves > 8) return false;
+  if (s.rtw % s.rsplit != 0) return false;
+  if (((int64_t)g.nslab * s.rsplit) % s.waves != 0) return false;
+  if (s.depth != 1 && s.depth != 2 && s.depth != 4) return false;
+  return true;
+}
+
+LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit) {
+  // Small search over (row tiles per workgroup, row splits, waves) with a crude
+  // cost: every wave pays a fixed set-up per (slab, split) item plus one unit per
+  // tile; a CU runs its resident waves four at a time (one per SIMD).
+  const int kCUs = 256;
+  const double setup = 1.2;
+  LaunchShape best{};
+  double best_cost = 1e300;
+  for (int rtw = 1; rtw <= g.n_rt && rtw <= 512; ++rtw) {
+    int32_t xpitch = 0;
+    const int32_t lds = lds_bytes_for(g, rtw, &xpitch);
+    if (lds > lds_limit) break;
+    const int nwg = (g.n_rt + rtw - 1) / rtw;
+    for (int rsplit = 1; rsplit <= rtw && rsplit <= 16; ++rsplit) {
+      if (rtw % rsplit) continue;
+      const int64_t items = (int64_t)g.nslab * rsplit;
+      for (int waves = 1; waves <= 8; ++waves) {
+        if (items % waves) continue;
+        const int ipw = (int)(items / waves);
+        const int iters = rtw / rsplit;
+        const double wave_work = ipw * (setup + iters);
+        int wg_per_cu = 8 / waves;
+        const int by_lds = lds_limit > 0 ? (160 * 1024) / (lds > 0 ? lds : 1) : 1;
+        if (wg_per_cu > by_lds) wg_per_cu = by_lds;
+        if (wg_per_cu < 1) wg_per_cu = 1;
+        const int rounds = (nwg + kCUs * wg_per_cu - 1) / (kCUs * wg_per_cu);
+        int wg_on_cu = (nwg + kCUs - 1) / kCUs;
+        if (wg_on_cu > wg_per_cu) wg_on_cu = wg_per_cu;
+        const int simd_load = (waves * wg_on_cu + 3) / 4;
+        double cost = rounds * simd_load * wave_work;
+        // with fewer workgroups than CUs part of the chip idles: charge for it
+        if (nwg < kCUs) cost *= 1.0 + 0.5 * (kCUs - nwg) / (double)kCUs;
+        cost += 1e-3 * waves - 1e-4 * iters;   // ties: fewer waves, more tiles per wave
+        if (cost < best_cost) {
+          best_cost = cost;
+          best.rtw = rtw; best.rsplit = rsplit; best.waves = waves;
+          best.nwg = nwg; best.lds_bytes = lds; best.xpitch = xpitch;
+        }
+      }
+    }
+  }
+  best.depth = 4;
+  return best;
+}
+
+}  // namespace owq
