@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Throughput of the OWQ mixed-precision linear layer on one MI355X.
+
+A step is one pass of the hot path over one token: every layer of the workload
+is called once through the C ABI (owq_linear), batch 1, on synthetic layers and
+activations that are already resident in HBM.  Successive steps use different
+packed copies of the layers (distinct addresses, more than the 256 MB of
+last-level cache in total), as successive decoder blocks of a model would, so
+that the weights really come from HBM.
+
+Prints ONE JSON line; see the design doc for the meaning of each field.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: (config index in the benchmark's list, layer indices, description)
+    "opt6.7b-ffn": (2, [0, 1], "configs[2]: OPT-6.7B-like FFN pair, fc1 4096->16384 (k=32) + fc2 16384->4096 (k=128), 3-bit, group 128, batch 1"),
+    "opt6.7b-attn": (1, [0], "configs[1]: OPT-6.7B-like attention projection 4096->4096, 3-bit per-channel, k=32, batch 1"),
+    "target": (5, [0], "bandwidth-target layer 16384->4096, 3-bit per-channel, k=128, batch 1"),
+    "llama13b": (3, [0, 1, 2], "configs[3]: LLaMA-13B-like q/k/v/o, gate/up, down, 4-bit group 128, k=1%"),
+    "tiny": (0, [0], "configs[0]: 1024->1024, 4-bit per-channel, k=8, batch 1"),
+}
+
+
+def algorithmic_bytes(spec, batch: int) -> int:
+    """Bytes one call has to move: codes + (scale, zero) + weak columns + indices + x + y."""
+    groups = 1 if spec.group_size == 0 else -(-spec.d_in // spec.group_size)
+    return (spec.d_out * spec.d_in * spec.bits // 8 + 4 * spec.d_out * groups + 2 * spec.d_out * spec.k
+            + 4 * spec.k + 2 * batch * (spec.d_in + spec.d_out))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="opt6.7b-ffn", choices=sorted(WORKLOADS))
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
+                    help="graph: the K timed steps are one HIP graph launch; eager: K*layers launches from Python")
+    ap.add_argument("--footprint-gb", type=float, default=1.5, help="total bytes of packed copies to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--launch", default="", help="rtw,rsplit,waves,depth override for every layer (tuning)")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2306_02272_amd import binding as B
+    from synth import CONFIGS, make_layer, make_x
+
+    B.lib()                                       # no library, no benchmark
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg, layer_ids, desc = WORKLOADS[args.workload]
+    specs = [CONFIGS[cfg][i] for i in layer_ids]
+    batch = args.batch
+
+    layers = [make_layer(s) for s in specs]
+    xs_host = [make_x(L, batch) for L in layers]
+    bytes_per_layer = [algorithmic_bytes(s, batch) for s in specs]
+    step_bytes = sum(bytes_per_layer)
+
+    # packed copies to rotate over
+    first = [B.OwqLinear(L) for L in layers]
+    packed_total = sum(int(f.buf.numel()) for f in first)
+    copies = max(1, int(-(-args.footprint_gb * 1e9 // packed_total)))
+    sets = [first] + [[B.OwqLinear(L, packed=f.buf) for L, f in zip(layers, first)] for _ in range(copies - 1)]
+    if args.launch:
+        rtw, rsplit, waves, depth = (int(v) for v in args.launch.split(","))
+        for st in sets:
+            for lin in st:
+                B.owq_set_launch(lin.handle, rtw, rsplit, waves, depth)
+    xs = [torch.from_numpy(x).cuda() for x in xs_host]
+    ys = [torch.empty((batch, s.d_out), dtype=torch.float16, device="cuda") for s in specs]
+
+    stream = torch.cuda.Stream()                  # default priority
+    raw = stream.cuda_stream
+
+    def run_steps(first_step: int, n: int):
+        for t in range(first_step, first_step + n):
+            st = sets[t % copies]
+            for lin, x, y in zip(st, xs, ys):
+                B.owq_linear(lin.handle, x.data_ptr(), y.data_ptr(), batch, raw)
+
+    with torch.cuda.stream(stream):
+        run_steps(0, args.warmup)
+        stream.synchronize()
+        graph = None
+        if args.mode == "graph":
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                run_steps(args.warmup, args.steps)
+            graph.replay()                        # untimed: uploads the graph
+            stream.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        if graph is not None:
+            graph.replay()
+        else:
+            run_steps(args.warmup, args.steps)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    wall_s = t1 - t0
+    event_s = ev0.elapsed_time(ev1) * 1e-3
+    ms_per_step = wall_s / args.steps * 1e3
+    value = step_bytes / (wall_s / args.steps) / 1e9
+
+    # parity of the last step against the oracle is checked in tests; here only a finite-ness guard
+    for y in ys:
+        assert torch.isfinite(y).all()
+
+    launches = args.steps * len(specs)
+    avg_launch_s = event_s / launches
+    achieved = (step_bytes / len(specs)) / avg_launch_s / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload)
+        except Exception:
+            traffic = None
+    info = first[0].info()
+    result = {
+        "metric": "effective HBM GB/s (% of peak) + us/call, 3-bit OWQ linear, batch 1",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 activations x 3/4-bit codes, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": desc, "batch": batch, "layers": [s.name for s in specs],
+                   "packed_copies": copies, "launch_mode": args.mode,
+                   "bytes_per_step": step_bytes},
+        "pct_of_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "us_per_call": round(wall_s / launches * 1e6, 3),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "kernel": f"owq_gemv_kernel<{specs[0].bits},{info.prefetch_depth}>",
+                     "avg_launch_us": round(avg_launch_s * 1e6, 3),
+                     "bytes_per_launch": step_bytes // len(specs)},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import owq_ref
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        c0 = time.perf_counter()
+        for L, x in zip(layers, xs_host):
+            owq_ref.owq_linear_layer(L, x)
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": round(step_bytes / (c1 - c0) / 1e9, 4), "unit": "GB/s",
+                                  "cores": int(threads), "kind": "oracle",
+                                  "sample": f"1 step ({len(specs)} full layers, batch {batch}) in {c1 - c0:.2f} s"}
+    print(json.dumps(result), flush=True)
+    for st in sets:
+        for lin in st:
+            lin.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
