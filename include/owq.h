@@ -36,7 +36,7 @@ typedef struct owq_layer_s *owq_handle_t; /* opaque; owned by the library until 
 typedef enum {
   OWQ_OK = 0,
   OWQ_ERR_NULL = 1,       /* a required pointer is NULL */
-  OWQ_ERR_SHAPE = 2,      /* d_out < 1, d_in < 1 or a size does not fit 32-bit indexing */
+  OWQ_ERR_SHAPE = 2,      /* d_out < 1, d_in < 1, or the packed layer would reach 4 GiB */
   OWQ_ERR_BITS = 3,       /* bits is neither 3 nor 4 */
   OWQ_ERR_GROUP = 4,      /* group_size is neither 0 nor a positive multiple of 128 */
   OWQ_ERR_CODE_RANGE = 5, /* a code at a non-weak column is >= 2^bits */
@@ -154,7 +154,7 @@ owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes);
 /*
  * Tuning hook for benchmarks: override the launch shape of the batch <= 16 path.
  * row_tiles_per_wg >= 1; row_splits divides row_tiles_per_wg; waves_per_wg in
- * [1, 8] divides nslab * row_splits; prefetch_depth in {1, 2, 4}.  A value of 0
+ * [1, 8] divides nslab * row_splits; prefetch_depth in {2, 4, 8} (8 only with at most 4 waves).  A value of 0
  * keeps the current setting.  Rejected shapes leave the handle unchanged.
  * Not thread-safe against concurrent owq_linear on the same handle.
  */

@@ -28,6 +28,8 @@ def build(verbose: bool = True, keep_asm: bool = False) -> str:
            "-Wall", "-Wno-unused-command-line-argument"]
     if keep_asm:
         cmd += ["-save-temps=obj"]
+    if os.environ.get("OWQ_TRACE"):      # developer aid: per-wave time stamps
+        cmd += ["-DOWQ_TRACE"]
     tmp_lib = os.path.join(out_dir, "libowq.so")
     cmd += ["-o", tmp_lib] + [os.path.join(HERE, "csrc", s) for s in SOURCES]
     if verbose:

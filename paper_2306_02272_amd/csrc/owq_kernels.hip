@@ -38,7 +38,8 @@ struct GemvArgs {
   const _Float16 *x;
   _Float16 *y;
   int d_in, d_out, nblk, cw, nact, nslab, n_rt, r, n_groups, blocks_per_group;
-  int kp, kchunks;
+  int k, kp, kchunks;
+  int xper;   // 16-byte activation units per thread (ceil)
   int rtw, rsplit, items, xpitch, ppitch;
 };
 
@@ -137,15 +138,75 @@ __device__ __forceinline__ float half_hi(u32 w) {
   return (float)__builtin_bit_cast(h2_t, w)[1];
 }
 
-template <int BITS, int DEPTH>
-__global__ __launch_bounds__(512) void owq_gemv_kernel(const GemvArgs a) {
+// One tile of one lane: 128 codes against the block's activations, then the
+// per-(row, block) epilogue  p = s * (acc - Bc - z * X) + weak chunk.
+template <int BITS, bool HAS_WEAK>
+__device__ __forceinline__ float tile_partial(const u32x4 *cb, u32 szw, const u32x4 &wkv, const u32x4 &xwr,
+                                              const u32 *xr, const Magic &M, float X, float Bc) {
+  float a0 = 0.f, a1 = 0.f;
+  if (BITS == 3) {
+    u32 w[12];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+      w[4 * c] = cb[c].x; w[4 * c + 1] = cb[c].y; w[4 * c + 2] = cb[c].z; w[4 * c + 3] = cb[c].w;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) mac_quad3(w[3 * u], w[3 * u + 1], w[3 * u + 2], &xr[16 * u], M, a0, a1);
+  } else {
+    u32 w[16];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      w[4 * c] = cb[c].x; w[4 * c + 1] = cb[c].y; w[4 * c + 2] = cb[c].z; w[4 * c + 3] = cb[c].w;
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mac_dword4(w[v], &xr[4 * v], M, a0, a1);
+  }
+  const float sc = half_lo(szw), zp = half_hi(szw);
+  float p = (a0 + a1) - Bc;
+  p = __builtin_fmaf(-zp, X, p);
+  p *= sc;
+  if (HAS_WEAK) {
+    p = dot2(wkv.x, xwr.x, p);
+    p = dot2(wkv.y, xwr.y, p);
+    p = dot2(wkv.z, xwr.z, p);
+    p = dot2(wkv.w, xwr.w, p);
+  }
+  return p;
+}
+
+// Developer aid (build with -DOWQ_TRACE): per-wave time stamps of the kernel's phases.
+#ifdef OWQ_TRACE
+__device__ long long g_trace[4096 * 16];
+#define TRACE(slot) do { if (lane == 0 && blockIdx.y == 0) g_trace[((blockIdx.x * nwaves + wave) & 4095) * 16 + (slot)] = (long long)wall_clock64(); } while (0)
+#else
+#define TRACE(slot) do { } while (0)
+#endif
+
+// Sum over the 16 lanes of a row of the wave (every lane gets the total), in a fixed order.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false));   // lanes ^1
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false));   // lanes ^2
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, false));  // mirror in 8
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, false));  // mirror in 16
+  return v;
+}
+
+// Template parameters: code width; tiles in flight per wave; whether the layer has
+// weak columns; XN = how many 16-byte units of activations a thread fetches into
+// registers ahead of the weight stream (needs x 16-byte aligned and d_in a multiple of
+// 8; 0 = general path with scalar loads).  Units beyond XN per thread follow in a loop.
+// With 8 tiles in flight a wave needs the register file of a whole SIMD: at most 4 waves
+// per workgroup then.
+template <int BITS, int DEPTH, bool HAS_WEAK, int XN>
+__global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const GemvArgs a) {
   constexpr int CH = BITS == 3 ? 3 : 4;
-  constexpr int XCH = 12;   // 16-byte activation units a thread stages from registers
+  constexpr bool FAST = XN > 0;
+  constexpr int XCH = FAST ? XN : 1;
   extern __shared__ uint4 smem[];
   uint4 *xs = smem;                                             // [16][xpitch] units of 8 fp16
   _Float16 *xs_h = reinterpret_cast<_Float16 *>(smem);
   const int xw_units = (a.kp * 2 + 15) >> 4;
-  uint4 *xw_u = smem + 16 * a.xpitch;                           // gathered weak activations
+  uint4 *xw_u = smem + 16 * a.xpitch;                           // activations of the weak columns
   _Float16 *xw = reinterpret_cast<_Float16 *>(xw_u);
   float *part = reinterpret_cast<float *>(xw_u + xw_units);     // [rows of the workgroup][ppitch]
 
@@ -154,212 +215,256 @@ __global__ __launch_bounds__(512) void owq_gemv_kernel(const GemvArgs a) {
   const _Float16 *xn = a.x + (size_t)blockIdx.y * a.d_in;
   _Float16 *yn = a.y + (size_t)blockIdx.y * a.d_out;
   const int nunits = a.nblk * 16;
-  const bool fast_x = ((reinterpret_cast<uintptr_t>(xn) & 15) == 0) && ((a.d_in & 7) == 0);
+  TRACE(0);
 
   const bool active = lane < a.nact;
   const int al = active ? lane : 0;
   const int rloc = al / a.cw, bloc = al - rloc * a.cw;
   const int rt0 = blockIdx.x * a.rtw;
   const int rt_end = min(a.n_rt, rt0 + a.rtw);
-  const int tile_units = CH * a.nact;
+  const u32 tile_bytes = (u32)(CH * a.nact) * 16u;
+  const u32 chunk_bytes = (u32)a.nact * 16u;
+  const char *codes_b = reinterpret_cast<const char *>(a.codes);
+  const char *sz_b = reinterpret_cast<const char *>(a.sz);
+  const char *wk_b = reinterpret_cast<const char *>(a.weak_w);
 
-  // ---- activations: global -> registers (first XCH units per thread) --------
+  // ---- (1) loads the set-up needs: activations and weak indices ------------------
+  // Issued before the weight stream: loads complete in order, so waiting for
+  // these does not wait for the weights behind them.  No branches: units past the
+  // end re-read unit 0 and are dropped below, so that the number of loads in
+  // flight is fixed and the waits can be exact.
   uint4 xv[XCH];
-  if (fast_x) {
+  int idx0 = -1;
+  if (FAST) {
 #pragma unroll
     for (int j = 0; j < XCH; ++j) {
       const int i = tid + j * nthr;
-      xv[j] = make_uint4(0, 0, 0, 0);
-      if (i < nunits && i * 8 < a.d_in) xv[j] = *reinterpret_cast<const uint4 *>(xn + i * 8);
+      const int ic = (i * 8 < a.d_in) ? i : 0;
+      xv[j] = *reinterpret_cast<const uint4 *>(xn + ic * 8);
     }
   }
+  if (HAS_WEAK) idx0 = a.weak_idx[tid < a.kp ? tid : 0];
 
-  // ---- per-item state and the tile pipeline ---------------------------------
+  // ---- (2) per-item state and the tile pipeline ---------------------------------
   u32x4 buf[DEPTH][CH];
   u32 szb[DEPTH];
   u32x4 wkb[DEPTH];
   int item = wave;
-  int s = 0, q = 0, blk = 0, grp = 0, niter = 0;
+  int blk = 0, niter = 0, niter_r = 0;
   bool wk = false;
+  u32 off_c = 0, off_s = 0, off_w = 0;       // byte offsets of the next tile to fetch
+  u32 str_c = 0, str_s = 0, str_w = 0;       // their strides per tile
+  int fetched = 0;                           // tiles fetched so far for this item
+  int pidx = 0, pstr = 0;                    // LDS index of the partial, stride per tile
 
   auto set_item = [&](int it_) {
-    s = it_ % a.nslab;
-    q = it_ / a.nslab;
+    const int s = it_ % a.nslab, q = it_ / a.nslab;
     blk = s * a.cw + bloc;
-    grp = a.blocks_per_group ? blk / a.blocks_per_group : 0;
+    const int grp = a.blocks_per_group ? blk / a.blocks_per_group : 0;
     const int span = rt_end - rt0 - q;
     niter = span > 0 ? (span + a.rsplit - 1) / a.rsplit : 0;
-    wk = active && blk < a.kchunks;
-  };
-  auto issue = [&](int d, int it) {
-    // Tiles past the end read unit 0 (always valid) so that the number of loads
-    // in flight never depends on data.
-    const bool live = it < niter;
-    const int rt = rt0 + q + it * a.rsplit;
-    const int base = live ? (rt * a.nslab + s) * tile_units + al : 0;
-    const int step = live ? a.nact : 0;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) buf[d][c] = __builtin_nontemporal_load(a.codes + base + c * step);
+    niter_r = (niter + DEPTH - 1) / DEPTH * DEPTH;
+    wk = HAS_WEAK && active && blk < a.kchunks;
+    const int rt = rt0 + q;
     const int row = rt * a.r + rloc;
-    szb[d] = a.sz[live ? row * a.n_groups + grp : 0];
-    if (a.kchunks) wkb[d] = __builtin_nontemporal_load(a.weak_w + ((live && wk) ? row * a.kchunks + blk : 0));
+    off_c = (u32)(rt * a.nslab + s) * tile_bytes + (u32)al * 16u;
+    str_c = (u32)(a.rsplit * a.nslab) * tile_bytes;
+    off_s = (u32)(row * a.n_groups + grp) * 4u;
+    str_s = (u32)(a.rsplit * a.r * a.n_groups) * 4u;
+    off_w = wk ? (u32)(row * a.kchunks + blk) * 16u : 0u;
+    str_w = wk ? (u32)(a.rsplit * a.r * a.kchunks) * 16u : 0u;
+    fetched = 0;
+    pidx = (q * a.r + rloc) * a.ppitch + blk;
+    pstr = a.rsplit * a.r * a.ppitch;
+  };
+  // Fetch the next tile into slot d.  Past the last tile every lane reads byte 0
+  // of its section instead (one cache line per load), so that the number of loads
+  // in flight is the same on every path.
+  auto issue = [&](int d) {
+    const bool live = fetched < niter;        // uniform
+    const u32 oc = live ? off_c : 0u, cs = live ? chunk_bytes : 0u;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+      buf[d][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes_b + (oc + (u32)c * cs)));
+    szb[d] = *reinterpret_cast<const u32 *>(sz_b + (live ? off_s : 0u));
+    if (HAS_WEAK)
+      wkb[d] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wk_b + (live ? off_w : 0u)));
+    off_c += str_c; off_s += str_s; off_w += str_w;
+    ++fetched;
   };
 
-  if (item < a.items) {
-    set_item(item);
+  set_item(item);                             // waves <= items: every wave has a first item
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) issue(d, d);
-  }
+  for (int d = 0; d < DEPTH; ++d) issue(d);
+  TRACE(1);
 
-  // ---- activations: registers -> LDS, transposed to [unit-in-block][block] ---
-  if (fast_x) {
+  // ---- (3) activations -> LDS, transposed to [unit-in-block][block] -------------
+  if (FAST) {
 #pragma unroll
     for (int j = 0; j < XCH; ++j) {
       const int i = tid + j * nthr;
-      if (i < nunits) xs[(i & 15) * a.xpitch + (i >> 4)] = xv[j];
+      if (i < nunits) xs[(i & 15) * a.xpitch + (i >> 4)] = (i * 8 < a.d_in) ? xv[j] : make_uint4(0, 0, 0, 0);
     }
-    for (int i = tid + XCH * nthr; i < nunits; i += nthr) {
+    for (int i = tid + XCH * nthr; i < nunits; i += nthr) {       // very wide layers only
       uint4 v = make_uint4(0, 0, 0, 0);
       if (i * 8 < a.d_in) v = *reinterpret_cast<const uint4 *>(xn + i * 8);
       xs[(i & 15) * a.xpitch + (i >> 4)] = v;
     }
   } else {
+    const bool vec = ((reinterpret_cast<uintptr_t>(xn) & 15) == 0) && ((a.d_in & 7) == 0);
     for (int i = tid; i < nunits; i += nthr) {
-      _Float16 e[8];
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (vec) {
+        if (i * 8 < a.d_in) v = *reinterpret_cast<const uint4 *>(xn + i * 8);
+      } else {
+        _Float16 e[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int j = i * 8 + t;
-        e[t] = j < a.d_in ? xn[j] : (_Float16)0;
+        for (int t = 0; t < 8; ++t) {
+          const int j = i * 8 + t;
+          e[t] = j < a.d_in ? xn[j] : (_Float16)0;
+        }
+        v = *reinterpret_cast<const uint4 *>(e);
       }
-      xs[(i & 15) * a.xpitch + (i >> 4)] = *reinterpret_cast<const uint4 *>(e);
+      xs[(i & 15) * a.xpitch + (i >> 4)] = v;
     }
   }
+  TRACE(2);
   __syncthreads();
-  // Gather the activations of the weak columns, then clear them in the staged
-  // copy: the dense path must contribute nothing there.
-  for (int t = tid; t < a.kp; t += nthr) {
-    const int j = a.weak_idx[t];
-    _Float16 v = (_Float16)0;
-    if (j >= 0) {
-      const int b = j >> 7, u = (j >> 3) & 15, e = j & 7;
-      const int pos = (u * a.xpitch + b) * 8 + e;
-      v = xs_h[pos];
-      xs_h[pos] = (_Float16)0;
-    }
-    xw[t] = v;
+  // Move the activations of the weak columns to their own array and clear them in
+  // the staged copy: the dense path must contribute nothing there.  The index list
+  // is the only layer data this waits for, and it is small.
+  if (HAS_WEAK) {
+    auto gather = [&](int t, int j) {
+      _Float16 v = (_Float16)0;
+      if (j >= 0) {
+        const int b = j >> 7, u = (j >> 3) & 15, e = j & 7;
+        const int pos = (u * a.xpitch + b) * 8 + e;
+        v = xs_h[pos];
+        xs_h[pos] = (_Float16)0;
+      }
+      xw[t] = v;
+    };
+    if (tid < a.kp) gather(tid, idx0);
+    for (int t = tid + nthr; t < a.kp; t += nthr) gather(t, a.weak_idx[t]);
+    __syncthreads();
   }
-  __syncthreads();
+  TRACE(3);
 
-  // ---- main loop over the wave's (slab, row split) items ----------------------
+  // ---- (4) main loop over the wave's (slab, row split) items ----------------------
   Magic M;
   M.init();
-  for (; item < a.items; item += nwaves) {
-    if (item != wave) {
-      set_item(item);
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) issue(d, d);
-    }
+  for (;;) {
     u32 xr[64];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
       const uint4 v = xs[u * a.xpitch + blk];
       xr[4 * u + 0] = v.x; xr[4 * u + 1] = v.y; xr[4 * u + 2] = v.z; xr[4 * u + 3] = v.w;
     }
+    u32x4 xwr = {0u, 0u, 0u, 0u};
+    if (HAS_WEAK) {
+      const uint4 t4 = xw_u[wk ? blk : 0];
+      if (wk) { xwr.x = t4.x; xwr.y = t4.y; xwr.z = t4.z; xwr.w = t4.w; }
+    }
     float X, Bc;
     block_sums<BITS>(xr, X, Bc);
-    uint4 xwr = make_uint4(0, 0, 0, 0);
-    if (wk) xwr = xw_u[blk];
+    TRACE(4);
 
-    for (int it0 = 0; it0 < niter; it0 += DEPTH) {
+    int it0 = 0;
+    // steady state: every tile of the trip is real; fetch DEPTH tiles ahead
+    for (; it0 + DEPTH < niter_r; it0 += DEPTH) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        const int it = it0 + d;
-        if (it < niter) {
-          float a0 = 0.f, a1 = 0.f;
-          if (BITS == 3) {
-            u32 w[12];
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-              w[4 * c] = buf[d][c].x; w[4 * c + 1] = buf[d][c].y; w[4 * c + 2] = buf[d][c].z; w[4 * c + 3] = buf[d][c].w;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) mac_quad3(w[3 * u], w[3 * u + 1], w[3 * u + 2], &xr[16 * u], M, a0, a1);
-          } else {
-            u32 w[16];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              w[4 * c] = buf[d][c].x; w[4 * c + 1] = buf[d][c].y; w[4 * c + 2] = buf[d][c].z; w[4 * c + 3] = buf[d][c].w;
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mac_dword4(w[v], &xr[4 * v], M, a0, a1);
-          }
-          const float sc = half_lo(szb[d]), zp = half_hi(szb[d]);
-          float p = (a0 + a1) - Bc;
-          p = __builtin_fmaf(-zp, X, p);
-          p *= sc;
-          if (a.kchunks) {
-            p = dot2(wkb[d].x, xwr.x, p);
-            p = dot2(wkb[d].y, xwr.y, p);
-            p = dot2(wkb[d].z, xwr.z, p);
-            p = dot2(wkb[d].w, xwr.w, p);
-          }
-          const int rt = rt0 + q + it * a.rsplit;
-          if (active) part[((rt - rt0) * a.r + rloc) * a.ppitch + blk] = p;
-          issue(d, it + DEPTH);
-        }
+        const float p = tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc);
+        if (active) part[pidx] = p;
+        pidx += pstr;
+        if (it0 == 0 && d < 4) TRACE(9 + d);
+        issue(d);
       }
     }
+    TRACE(5);
+    // last trip: nothing more to fetch; tiles past the end are computed on filler and dropped
+    if (niter_r > 0) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const float p = tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc);
+        if (active && it0 + d < niter) part[pidx] = p;
+        pidx += pstr;
+      }
+    }
+    TRACE(6);
+    item += nwaves;
+    if (item >= a.items) break;
+    set_item(item);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) issue(d);
   }
   __syncthreads();
+  TRACE(7);
 
-  // ---- add the partials of each row; weak chunks beyond one per block -------
+  // ---- (5) add the partials of each row; weak chunks beyond one per block -------
   const int rows_here = (rt_end - rt0) * a.r;
   const int l16 = tid & 15;
   for (int rs = tid >> 4; rs < rows_here; rs += nthr >> 4) {
     const int row = rt0 * a.r + rs;
-    float sum = 0.f;
-    for (int b = l16; b < a.nblk; b += 16) sum += part[rs * a.ppitch + b];
-    for (int c = a.nblk + l16; c < a.kchunks; c += 16) {
-      const u32x4 wv = a.weak_w[row * a.kchunks + c];
-      const uint4 xv4 = xw_u[c];
-      sum = dot2(wv.x, xv4.x, sum);
-      sum = dot2(wv.y, xv4.y, sum);
-      sum = dot2(wv.z, xv4.z, sum);
-      sum = dot2(wv.w, xv4.w, sum);
+    const float *pr = part + rs * a.ppitch;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    for (int b = l16; b < a.nblk; b += 64) {              // four independent LDS reads per trip
+      s0 += pr[b];
+      s1 += (b + 16 < a.nblk) ? pr[b + 16] : 0.f;
+      s2 += (b + 32 < a.nblk) ? pr[b + 32] : 0.f;
+      s3 += (b + 48 < a.nblk) ? pr[b + 48] : 0.f;
     }
-    sum += __shfl_xor(sum, 1, 16);
-    sum += __shfl_xor(sum, 2, 16);
-    sum += __shfl_xor(sum, 4, 16);
-    sum += __shfl_xor(sum, 8, 16);
+    float sum = (s0 + s1) + (s2 + s3);
+    if (HAS_WEAK) {
+      for (int c = a.nblk + l16; c < a.kchunks; c += 16) {
+        const u32x4 wv = a.weak_w[row * a.kchunks + c];
+        const uint4 xv4 = xw_u[c];
+        sum = dot2(wv.x, xv4.x, sum);
+        sum = dot2(wv.y, xv4.y, sum);
+        sum = dot2(wv.z, xv4.z, sum);
+        sum = dot2(wv.w, xv4.w, sum);
+      }
+    }
+    sum = row16_sum(sum);
     if (l16 == 0 && row < a.d_out) yn[row] = (_Float16)sum;
   }
+  TRACE(8);
 }
 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 
-template <int BITS, int DEPTH>
-static hipError_t launch_one(const GemvArgs &args, dim3 grid, dim3 block, int lds, hipStream_t st) {
-  hipLaunchKernelGGL((owq_gemv_kernel<BITS, DEPTH>), grid, block, lds, st, args);
-  return hipGetLastError();
+typedef void (*kernel_fn)(const GemvArgs);
+
+template <int BITS, int DEPTH, bool WEAK>
+static kernel_fn pick3(int xn) {
+  if (xn == 4) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4>;
+  if (xn == 8) return owq_gemv_kernel<BITS, DEPTH, WEAK, 8>;
+  return owq_gemv_kernel<BITS, DEPTH, WEAK, 0>;
 }
 
-template <int BITS, int DEPTH>
-static hipError_t raise_lds(int lds) {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(&owq_gemv_kernel<BITS, DEPTH>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+template <int BITS>
+static kernel_fn pick2(int depth, bool weak, int xn) {
+  if (depth == 2) return weak ? pick3<BITS, 2, true>(xn) : pick3<BITS, 2, false>(xn);
+  if (depth == 4) return weak ? pick3<BITS, 4, true>(xn) : pick3<BITS, 4, false>(xn);
+  return weak ? pick3<BITS, 8, true>(xn) : pick3<BITS, 8, false>(xn);
+}
+
+static kernel_fn pick(int bits, int depth, bool weak, int xn) {
+  return bits == 3 ? pick2<3>(depth, weak, xn) : pick2<4>(depth, weak, xn);
 }
 
 int prepare_kernels(int32_t lds) {
   if (lds <= 64 * 1024) return (int)hipSuccess;
-  hipError_t e;
-  if ((e = raise_lds<3, 1>(lds)) != hipSuccess) return (int)e;
-  if ((e = raise_lds<3, 2>(lds)) != hipSuccess) return (int)e;
-  if ((e = raise_lds<3, 4>(lds)) != hipSuccess) return (int)e;
-  if ((e = raise_lds<4, 1>(lds)) != hipSuccess) return (int)e;
-  if ((e = raise_lds<4, 2>(lds)) != hipSuccess) return (int)e;
-  if ((e = raise_lds<4, 4>(lds)) != hipSuccess) return (int)e;
+  for (int bits = 3; bits <= 4; ++bits)
+    for (int depth = 2; depth <= 8; depth *= 2)
+      for (int w = 0; w < 2; ++w)
+        for (int xn = 0; xn <= 8; xn += 4) {
+          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(bits, depth, w, xn)),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+          if (e != hipSuccess) return (int)e;
+        }
   return (int)hipSuccess;
 }
 
@@ -386,23 +491,26 @@ int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLay
   a.d_in = g.d_in; a.d_out = g.d_out; a.nblk = g.nblk; a.cw = g.cw; a.nact = g.nact;
   a.nslab = g.nslab; a.n_rt = g.n_rt; a.r = g.r; a.n_groups = g.n_groups;
   a.blocks_per_group = g.group_size ? g.group_size / kBlockCols : 0;
-  a.kp = g.kp; a.kchunks = g.kp / 8;
+  a.k = g.k; a.kp = g.kp; a.kchunks = g.kp / 8;
   a.rtw = s.rtw; a.rsplit = s.rsplit; a.items = g.nslab * s.rsplit;
   a.xpitch = s.xpitch;
   a.ppitch = g.nblk;
-  const dim3 grid((unsigned)s.nwg, (unsigned)batch, 1), block((unsigned)s.waves * 64, 1, 1);
+  const int nthr = s.waves * 64;
+  a.xper = (g.nblk * 16 + nthr - 1) / nthr;
+  // 16-byte staging from registers needs aligned rows
+  const bool aligned = (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (g.d_in % 8 == 0);
+  const int xn = !aligned ? 0 : (a.xper <= 4 ? 4 : 8);
+  const dim3 grid((unsigned)s.nwg, (unsigned)batch, 1), block((unsigned)nthr, 1, 1);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipError_t e = hipErrorInvalidValue;
-  if (g.bits == 3) {
-    if (s.depth == 1) e = launch_one<3, 1>(a, grid, block, s.lds_bytes, st);
-    else if (s.depth == 2) e = launch_one<3, 2>(a, grid, block, s.lds_bytes, st);
-    else if (s.depth == 4) e = launch_one<3, 4>(a, grid, block, s.lds_bytes, st);
-  } else {
-    if (s.depth == 1) e = launch_one<4, 1>(a, grid, block, s.lds_bytes, st);
-    else if (s.depth == 2) e = launch_one<4, 2>(a, grid, block, s.lds_bytes, st);
-    else if (s.depth == 4) e = launch_one<4, 4>(a, grid, block, s.lds_bytes, st);
-  }
-  return (int)e;
+  kernel_fn fn = pick(g.bits, s.depth, g.kp > 0, xn);
+  hipLaunchKernelGGL(fn, grid, block, s.lds_bytes, st, a);
+  return (int)hipGetLastError();
 }
 
 }  // namespace owq
+
+#ifdef OWQ_TRACE
+extern "C" int owq_debug_read_trace(long long *host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(owq::g_trace), sizeof(long long) * 4096 * 16);
+}
+#endif

@@ -46,10 +46,8 @@ owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t
   g->off_weak_w = align_up(g->off_sz + (uint64_t)g->d_out_pad * g->n_groups * 4);
   g->off_weak_idx = align_up(g->off_weak_w + (uint64_t)g->d_out_pad * g->kp * 2);
   g->total_bytes = align_up(g->off_weak_idx + (uint64_t)g->kp * 4);
-  // The kernels index 16-byte units and rows with 32-bit integers.
-  if (g->total_bytes / 16 >= (1ull << 31)) return OWQ_ERR_SHAPE;
-  if ((uint64_t)g->d_out_pad * (uint64_t)(g->n_groups > g->kp ? g->n_groups : g->kp) >= (1ull << 31))
-    return OWQ_ERR_SHAPE;
+  // The kernels address the blob with 32-bit byte offsets.
+  if (g->total_bytes >= (1ull << 32)) return OWQ_ERR_SHAPE;
   return OWQ_OK;
 }
 
@@ -142,6 +140,7 @@ void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *ou
 
   int32_t *ix = reinterpret_cast<int32_t *>(out + g.off_weak_idx);
   for (int32_t t = 0; t < g.kp; ++t) ix[t] = t < g.k ? d->weak_idx[t] : -1;
+
 }
 
 // ---------------------------------------------------------------------------
@@ -162,43 +161,46 @@ bool shape_is_valid(const owq_layer_info_t &g, const LaunchShape &s) {
   if (s.rtw < 1 || s.rsplit < 1 || s.waves < 1 || s.waves > 8) return false;
   if (s.rtw % s.rsplit != 0) return false;
   if (((int64_t)g.nslab * s.rsplit) % s.waves != 0) return false;
-  if (s.depth != 1 && s.depth != 2 && s.depth != 4) return false;
+  if (s.depth != 2 && s.depth != 4 && s.depth != 8) return false;
+  if (s.depth == 8 && s.waves > 4) return false;   // that variant is built for 256 threads at most
   return true;
 }
 
 LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit) {
-  // Small search over (row tiles per workgroup, row splits, waves) with a crude
-  // cost: every wave pays a fixed set-up per (slab, split) item plus one unit per
-  // tile; a CU runs its resident waves four at a time (one per SIMD).
+  // Small search over (row tiles per workgroup, row splits, waves per workgroup) with a
+  // cost model fitted to measurements on MI355X, in units of one tile of one wave:
+  // a launch pays a fixed start-up (first bytes from HBM), every wave pays a set-up per
+  // (slab, split) item plus its tiles, waves beyond one per SIMD share the SIMD, and
+  // staging the activations costs in proportion to the 16-byte units per thread.
   const int kCUs = 256;
-  const double setup = 1.2;
+  const double startup = 6.0, setup = 1.0, stage_per_unit = 0.2;
   LaunchShape best{};
   double best_cost = 1e300;
-  for (int rtw = 1; rtw <= g.n_rt && rtw <= 512; ++rtw) {
+  for (int rtw = 1; rtw <= g.n_rt && rtw <= 1024; ++rtw) {
     int32_t xpitch = 0;
     const int32_t lds = lds_bytes_for(g, rtw, &xpitch);
     if (lds > lds_limit) break;
     const int nwg = (g.n_rt + rtw - 1) / rtw;
-    for (int rsplit = 1; rsplit <= rtw && rsplit <= 16; ++rsplit) {
+    for (int rsplit = 1; rsplit <= rtw && rsplit <= 8; ++rsplit) {
       if (rtw % rsplit) continue;
       const int64_t items = (int64_t)g.nslab * rsplit;
       for (int waves = 1; waves <= 8; ++waves) {
         if (items % waves) continue;
         const int ipw = (int)(items / waves);
         const int iters = rtw / rsplit;
-        const double wave_work = ipw * (setup + iters);
-        int wg_per_cu = 8 / waves;
-        const int by_lds = lds_limit > 0 ? (160 * 1024) / (lds > 0 ? lds : 1) : 1;
+        int wg_per_cu = 8 / waves;                       // at most two waves per SIMD
+        const int by_lds = (160 * 1024) / (lds > 0 ? lds : 1);
         if (wg_per_cu > by_lds) wg_per_cu = by_lds;
         if (wg_per_cu < 1) wg_per_cu = 1;
         const int rounds = (nwg + kCUs * wg_per_cu - 1) / (kCUs * wg_per_cu);
         int wg_on_cu = (nwg + kCUs - 1) / kCUs;
         if (wg_on_cu > wg_per_cu) wg_on_cu = wg_per_cu;
-        const int simd_load = (waves * wg_on_cu + 3) / 4;
-        double cost = rounds * simd_load * wave_work;
-        // with fewer workgroups than CUs part of the chip idles: charge for it
-        if (nwg < kCUs) cost *= 1.0 + 0.5 * (kCUs - nwg) / (double)kCUs;
-        cost += 1e-3 * waves - 1e-4 * iters;   // ties: fewer waves, more tiles per wave
+        const int share = (waves * wg_on_cu + 3) / 4;    // waves per SIMD
+        const double units_per_thread = (double)g.nblk * 16 / (waves * 64);
+        const double wave_work = ipw * (setup + iters) * share + stage_per_unit * units_per_thread * wg_on_cu;
+        double cost = rounds * (startup + wave_work);
+        if (nwg < kCUs) cost *= 1.0 + 0.5 * (kCUs - nwg) / (double)kCUs;   // idle CUs
+        cost += 1e-3 * waves - 1e-4 * iters;             // ties: fewer waves, more tiles per wave
         if (cost < best_cost) {
           best_cost = cost;
           best.rtw = rtw; best.rsplit = rsplit; best.waves = waves;
@@ -207,7 +209,7 @@ LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit) {
       }
     }
   }
-  best.depth = 4;
+  best.depth = 2;
   return best;
 }
 

@@ -166,7 +166,7 @@ def test_launch_shapes_do_not_change_the_result(env):
     want = owq_ref.owq_linear_layer(layer, x)
     lin = B.OwqLinear(layer)
     xd = torch.from_numpy(x).cuda()
-    for rtw, rsplit, waves, depth in [(1, 1, 1, 1), (1, 1, 2, 4), (8, 2, 4, 2), (16, 4, 8, 4), (64, 1, 2, 4), (5, 5, 2, 1)]:
+    for rtw, rsplit, waves, depth in [(1, 1, 1, 2), (1, 1, 2, 4), (8, 2, 4, 2), (16, 4, 8, 4), (64, 1, 2, 4), (5, 5, 2, 2), (16, 2, 4, 8), (7, 1, 1, 8)]:
         B.owq_set_launch(lin.handle, rtw, rsplit, waves, depth)
         info = lin.info()
         print("shape", rtw, rsplit, waves, depth, "->", info.workgroups, info.lds_bytes, flush=True)
