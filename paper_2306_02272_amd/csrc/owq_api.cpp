@@ -189,6 +189,7 @@ owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t
   s.lds_bytes = lds_bytes_for(h->info, s.rtw, &s.xpitch);
   if (s.lds_bytes > h->lds_limit) return OWQ_ERR_UNSUPPORTED;
   s.nwg = (h->info.n_rt + s.rtw - 1) / s.rtw;
+  if (!make_magics(h->info, &s)) return OWQ_ERR_UNSUPPORTED;
   h->shape = s;
   return OWQ_OK;
 }

@@ -31,7 +31,12 @@ struct LaunchShape {
   int32_t nwg;      // workgroups per batch row
   int32_t lds_bytes;
   int32_t xpitch;   // pitch (in 16-byte units) of the staged activations
+  // 16-bit reciprocals for the kernel's small divisions; 0 = not representable
+  uint32_t cw_magic, nslab_magic, rsplit_magic, bpg_magic;
 };
+
+// Fills the reciprocals of s for layer g; false if some division cannot be done that way.
+bool make_magics(const owq_layer_info_t &g, LaunchShape *s);
 
 bool shape_is_valid(const owq_layer_info_t &g, const LaunchShape &s);
 int32_t lds_bytes_for(const owq_layer_info_t &g, int32_t rtw, int32_t *xpitch);

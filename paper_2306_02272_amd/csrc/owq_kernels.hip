@@ -40,6 +40,8 @@ struct GemvArgs {
   int d_in, d_out, nblk, cw, nact, nslab, n_rt, r, n_groups, blocks_per_group;
   int k, kp, kchunks;
   int xper;   // 16-byte activation units per thread (ceil)
+  // host-made reciprocals: n / d == (n * magic) >> 16 for the small n that occur (checked on the host)
+  u32 cw_magic, nslab_magic, rsplit_magic, bpg_magic;
   int rtw, rsplit, items, xpitch, ppitch;
 };
 
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   float *part = reinterpret_cast<float *>(xw_u + xw_units);     // [rows of the workgroup][ppitch]
 
   const int tid = threadIdx.x, nthr = blockDim.x;
-  const int lane = tid & 63, wave = tid >> 6, nwaves = nthr >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
   const _Float16 *xn = a.x + (size_t)blockIdx.y * a.d_in;
   _Float16 *yn = a.y + (size_t)blockIdx.y * a.d_out;
   const int nunits = a.nblk * 16;
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 
   const bool active = lane < a.nact;
   const int al = active ? lane : 0;
-  const int rloc = al / a.cw, bloc = al - rloc * a.cw;
+  const int rloc = (int)(((u32)al * a.cw_magic) >> 16), bloc = al - rloc * a.cw;
   const int rt0 = blockIdx.x * a.rtw;
   const int rt_end = min(a.n_rt, rt0 + a.rtw);
   const u32 tile_bytes = (u32)(CH * a.nact) * 16u;
@@ -258,11 +260,11 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   int pidx = 0, pstr = 0;                    // LDS index of the partial, stride per tile
 
   auto set_item = [&](int it_) {
-    const int s = it_ % a.nslab, q = it_ / a.nslab;
+    const int q = (int)(((u32)it_ * a.nslab_magic) >> 16), s = it_ - q * a.nslab;
     blk = s * a.cw + bloc;
-    const int grp = a.blocks_per_group ? blk / a.blocks_per_group : 0;
+    const int grp = a.blocks_per_group ? (int)(((u32)blk * a.bpg_magic) >> 16) : 0;
     const int span = rt_end - rt0 - q;
-    niter = span > 0 ? (span + a.rsplit - 1) / a.rsplit : 0;
+    niter = span > 0 ? (int)(((u32)(span + a.rsplit - 1) * a.rsplit_magic) >> 16) : 0;
     niter_r = (niter + DEPTH - 1) / DEPTH * DEPTH;
     wk = HAS_WEAK && active && blk < a.kchunks;
     const int rt = rt0 + q;
@@ -293,9 +295,12 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     ++fetched;
   };
 
+  // Only the first two tiles go out ahead of the activations' arrival: more would
+  // queue up in front of the set-up's own loads and delay it.
+  constexpr int EARLY = DEPTH < 2 ? DEPTH : 2;
   set_item(item);                             // waves <= items: every wave has a first item
 #pragma unroll
-  for (int d = 0; d < DEPTH; ++d) issue(d);
+  for (int d = 0; d < EARLY; ++d) issue(d);
   TRACE(1);
 
   // ---- (3) activations -> LDS, transposed to [unit-in-block][block] -------------
@@ -328,6 +333,8 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
       xs[(i & 15) * a.xpitch + (i >> 4)] = v;
     }
   }
+#pragma unroll
+  for (int d = EARLY; d < DEPTH; ++d) issue(d);   // the activations have arrived: fill the pipeline
   TRACE(2);
   __syncthreads();
   // Move the activations of the weak columns to their own array and clear them in
@@ -497,6 +504,8 @@ int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLay
   a.ppitch = g.nblk;
   const int nthr = s.waves * 64;
   a.xper = (g.nblk * 16 + nthr - 1) / nthr;
+  a.cw_magic = s.cw_magic; a.nslab_magic = s.nslab_magic; a.rsplit_magic = s.rsplit_magic;
+  a.bpg_magic = s.bpg_magic;
   // 16-byte staging from registers needs aligned rows
   const bool aligned = (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (g.d_in % 8 == 0);
   const int xn = !aligned ? 0 : (a.xper <= 4 ? 4 : 8);

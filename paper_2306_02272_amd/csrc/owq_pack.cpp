@@ -157,6 +157,25 @@ int32_t lds_bytes_for(const owq_layer_info_t &g, int32_t rtw, int32_t *xpitch) {
   return total > 0x7fffffff ? 0x7fffffff : (int32_t)total;
 }
 
+// magic such that n / d == (n * magic) >> 16 for every n in [0, nmax]; 0 if there is none
+static uint32_t magic16(uint32_t d, uint32_t nmax) {
+  if (d == 0) return 0;
+  const uint32_t m = 65536u / d + 1u;
+  if ((uint64_t)nmax * m >= (1ull << 32)) return 0;
+  for (uint32_t n = 0; n <= nmax; ++n)
+    if (((n * m) >> 16) != n / d) return 0;
+  return m;
+}
+
+bool make_magics(const owq_layer_info_t &g, LaunchShape *s) {
+  s->cw_magic = magic16((uint32_t)g.cw, 63);
+  s->nslab_magic = magic16((uint32_t)g.nslab, (uint32_t)(g.nslab * s->rsplit));
+  s->rsplit_magic = magic16((uint32_t)s->rsplit, (uint32_t)(s->rtw + s->rsplit));
+  const uint32_t bpg = g.group_size ? (uint32_t)(g.group_size / kBlockCols) : 1u;
+  s->bpg_magic = magic16(bpg, (uint32_t)g.nblk);
+  return s->cw_magic && s->nslab_magic && s->rsplit_magic && s->bpg_magic;
+}
+
 bool shape_is_valid(const owq_layer_info_t &g, const LaunchShape &s) {
   if (s.rtw < 1 || s.rsplit < 1 || s.waves < 1 || s.waves > 8) return false;
   if (s.rtw % s.rsplit != 0) return false;
@@ -210,6 +229,7 @@ LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit) {
     }
   }
   best.depth = 2;
+  if (best.rtw >= 1 && !make_magics(g, &best)) best.rtw = 0;
   return best;
 }
 
