@@ -38,6 +38,22 @@ Blob = four sections, each starting on a 256-byte boundary, in this order:
   weak_w    d_out_pad * kp fp16, row-major, kp = k rounded up to a multiple of
             8, padding 0.
   weak_idx  kp int32, padding -1.
+
+Tile layout (layout = 1, for batched calls on the matrix cores).  Same sections,
+with these differences:
+  * a tile is 32 rows by one *block pair* (256 consecutive columns); nbp =
+    ceil(d_in / 256), nblk = 2 * nbp, n_rt = ceil(d_out / 32), all 64 lanes busy.
+    Lane a stands for row rt*32 + a % 32 and half kg = a // 32 of both blocks:
+    its 128 codes are "lane columns" c = 64*b + 8*t + e  (b = 0, 1 the block of the
+    pair, t = 0..7, e = 0..7) and lane column c is input column
+    256*bp + 128*b + 16*t + 8*kg + e.  The 128 lane columns are packed into the
+    lane's dwords exactly as the 128 columns of a block are in layout 0.
+    Tiles are ordered [row tile][block pair]; a tile is [chunk][lane][16 bytes].
+  * sz and weak_w have n_rt*32 rows.
+  * two more sections follow weak_idx: wmask, one byte per 8 input columns
+    (bit e = column 8i+e is weak), nbp*32 bytes; and a scratch area the library
+    uses at run time (contents undefined, zero in a fresh blob) of
+    64*(nbp*256)*2 + nblk*64*8 + 64*kp*2 + 8*64*(n_rt*32)*4 bytes.
 """
 from __future__ import annotations
 
@@ -71,6 +87,10 @@ class Geometry:
     off_weak_w: int
     off_weak_idx: int
     total_bytes: int
+    layout: int = 0
+    nbp: int = 0
+    off_wmask: int = 0
+    off_scratch: int = 0
 
 
 def _align(n: int) -> int:
@@ -85,9 +105,33 @@ def tile_shape(nblk: int):
     return best, 64 // best
 
 
-def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int) -> Geometry:
+TILE_ROWS = 32
+SCRATCH_BATCH = 64
+SCRATCH_SPLITS = 8
+
+
+def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int, layout: int = 0) -> Geometry:
     assert bits in (3, 4) and d_out >= 1 and d_in >= 1 and 0 <= k <= d_in
     assert group_size == 0 or group_size % BLOCK == 0
+    if layout == 1:
+        nbp = -(-d_in // (2 * BLOCK))
+        nblk = 2 * nbp
+        n_rt = -(-d_out // TILE_ROWS)
+        d_out_pad = n_rt * TILE_ROWS
+        chunks = 3 if bits == 3 else 4
+        n_groups = 1 if group_size == 0 else -(-d_in // group_size)
+        kp = -(-k // 8) * 8
+        off_sz = _align(n_rt * nbp * 64 * chunks * 16)
+        off_weak_w = _align(off_sz + d_out_pad * n_groups * 4)
+        off_weak_idx = _align(off_weak_w + d_out_pad * kp * 2)
+        off_wmask = _align(off_weak_idx + kp * 4)
+        off_scratch = _align(off_wmask + nbp * 32)
+        scratch = (SCRATCH_BATCH * nbp * 256 * 2 + nblk * SCRATCH_BATCH * 8 + SCRATCH_BATCH * kp * 2
+                   + SCRATCH_SPLITS * SCRATCH_BATCH * d_out_pad * 4)
+        total = _align(off_scratch + scratch)
+        return Geometry(d_out, d_in, bits, group_size, k, nblk, 1, TILE_ROWS, 64, nbp, n_rt,
+                        d_out_pad, chunks, n_groups, kp, 0, off_sz, off_weak_w, off_weak_idx,
+                        total, 1, nbp, off_wmask, off_scratch)
     nblk = -(-d_in // BLOCK)
     cw, r = tile_shape(nblk)
     nact = r * cw
@@ -139,6 +183,13 @@ def pack_codes(codes: np.ndarray, geo: Geometry) -> np.ndarray:
     assert int(codes.max(initial=0)) < (1 << geo.bits)
     full = np.zeros((geo.d_out_pad, geo.nblk * BLOCK), dtype=np.uint8)
     full[:geo.d_out, :geo.d_in] = codes
+    if geo.layout == 1:
+        # [rt, row, bp, b, t, kg, e] -> lanes [rt, bp, kg, row] with lane columns [b, t, e]
+        t = full.reshape(geo.n_rt, TILE_ROWS, geo.nbp, 2, 8, 2, 8)
+        t = t.transpose(0, 2, 5, 1, 3, 4, 6).reshape(geo.n_rt, geo.nbp, 64, BLOCK)
+        dw = _lane_dwords(t, geo.bits).reshape(geo.n_rt, geo.nbp, 64, geo.chunks, 4)
+        dw = dw.transpose(0, 1, 3, 2, 4)
+        return np.ascontiguousarray(dw).astype("<u4").view(np.uint8).reshape(-1)
     t = full.reshape(geo.n_rt, geo.r, geo.nslab, geo.cw, BLOCK)
     t = t.transpose(0, 2, 1, 3, 4).reshape(geo.n_rt, geo.nslab, geo.nact, BLOCK)
     dw = _lane_dwords(t, geo.bits)                                  # [rt, s, a, C*4]
@@ -147,12 +198,12 @@ def pack_codes(codes: np.ndarray, geo: Geometry) -> np.ndarray:
     return np.ascontiguousarray(dw).astype("<u4").view(np.uint8).reshape(-1)
 
 
-def pack_layer(codes, scale, zero, group_size, weak_idx, weak_w, bits) -> tuple[np.ndarray, Geometry]:
+def pack_layer(codes, scale, zero, group_size, weak_idx, weak_w, bits, layout: int = 0) -> tuple[np.ndarray, Geometry]:
     """The whole blob (uint8) and its geometry.  Codes at weak columns are stored as 0."""
     codes = np.array(codes, dtype=np.uint8, copy=True)
     d_out, d_in = codes.shape
     idx = np.asarray(weak_idx, dtype=np.int32)
-    geo = geometry(d_out, d_in, bits, group_size, int(idx.size))
+    geo = geometry(d_out, d_in, bits, group_size, int(idx.size), layout)
     codes[:, idx] = 0
     blob = np.zeros(geo.total_bytes, dtype=np.uint8)
     sec = pack_codes(codes, geo)
@@ -175,6 +226,12 @@ def pack_layer(codes, scale, zero, group_size, weak_idx, weak_w, bits) -> tuple[
     ix[:geo.k] = idx
     b = ix.astype("<i4").view(np.uint8).reshape(-1)
     blob[geo.off_weak_idx:geo.off_weak_idx + b.size] = b
+
+    if geo.layout == 1:
+        is_weak = np.zeros(geo.nbp * 256, dtype=np.uint8)
+        is_weak[idx] = 1
+        b = np.packbits(is_weak.reshape(-1, 8), axis=1, bitorder="little").reshape(-1)
+        blob[geo.off_wmask:geo.off_wmask + b.size] = b
     return blob, geo
 
 
@@ -182,11 +239,37 @@ def pack_layer(codes, scale, zero, group_size, weak_idx, weak_w, bits) -> tuple[
 # unpacker (inverse of pack_codes), written as a gather over bit positions
 # ---------------------------------------------------------------------------
 
+def _unpack_lanes(dw: np.ndarray, bits: int) -> np.ndarray:
+    """[..., C*4] dwords of a lane -> [..., 128] uint8 lane columns (inverse of _lane_dwords)."""
+    lead = dw.shape[:-1]
+    if bits == 3:
+        q = dw.reshape(lead + (4, 3)).astype(np.uint64)
+        lo = np.zeros(q.shape[:-1], dtype=np.uint64)
+        hi = np.zeros(q.shape[:-1], dtype=np.uint64)
+        for w in range(3):
+            lo |= (q[..., w] & np.uint64(0xFFFF)) << np.uint64(16 * w)
+            hi |= (q[..., w] >> np.uint64(16)) << np.uint64(16 * w)
+        sh = 3 * np.arange(16, dtype=np.uint64)
+        c = np.stack([(lo[..., None] >> sh) & np.uint64(7), (hi[..., None] >> sh) & np.uint64(7)], axis=-1)
+    else:
+        q = dw.astype(np.uint32)
+        sh = 4 * np.arange(4, dtype=np.uint32)
+        c = np.stack([((q & np.uint32(0xFFFF))[..., None] >> sh) & np.uint32(15),
+                      ((q >> np.uint32(16))[..., None] >> sh) & np.uint32(15)], axis=-1)
+    return c.astype(np.uint8).reshape(lead + (BLOCK,))
+
+
 def unpack_codes(blob: np.ndarray, geo: Geometry) -> np.ndarray:
     """Codes section of a blob -> uint8 [d_out, d_in]."""
     n_dw = geo.d_out_pad * geo.nblk * geo.chunks * 4
     dw = np.frombuffer(np.asarray(blob, dtype=np.uint8).tobytes(), dtype="<u4",
                        count=n_dw, offset=geo.off_codes)
+    if geo.layout == 1:
+        lanes = _unpack_lanes(dw.reshape(geo.n_rt, geo.nbp, geo.chunks, 64, 4).transpose(0, 1, 3, 2, 4)
+                              .reshape(geo.n_rt, geo.nbp, 64, geo.chunks * 4), geo.bits)
+        t = lanes.reshape(geo.n_rt, geo.nbp, 2, TILE_ROWS, 2, 8, 8)          # [rt, bp, kg, row, b, t, e]
+        full = t.transpose(0, 3, 1, 4, 5, 2, 6).reshape(geo.d_out_pad, geo.nblk * BLOCK)
+        return np.ascontiguousarray(full[:geo.d_out, :geo.d_in])
     dw = dw.reshape(geo.n_rt, geo.nslab, geo.chunks, geo.nact, 4)
     dw = dw.transpose(0, 1, 3, 2, 4).reshape(geo.n_rt, geo.nslab, geo.nact, geo.chunks * 4)
     if geo.bits == 3:
@@ -228,11 +311,21 @@ def unpack_params(blob: np.ndarray, geo: Geometry):
 
 def bit_address(geo: Geometry, row: int, col: int, bitno: int):
     """(byte offset in the blob, bit within that byte) of bit `bitno` of code (row, col)."""
-    rt, rloc = divmod(row, geo.r)
-    blk, cin = divmod(col, BLOCK)
-    s, bloc = divmod(blk, geo.cw)
-    lane = rloc * geo.cw + bloc
-    tile = rt * geo.nslab + s
+    if geo.layout == 1:
+        rt, rloc = divmod(row, TILE_ROWS)
+        bp, c256 = divmod(col, 2 * BLOCK)
+        b, c128 = divmod(c256, BLOCK)
+        t16, c16 = divmod(c128, 16)
+        kg, e = divmod(c16, 8)
+        lane = kg * TILE_ROWS + rloc
+        tile = rt * geo.nbp + bp
+        cin = 64 * b + 8 * t16 + e
+    else:
+        rt, rloc = divmod(row, geo.r)
+        blk, cin = divmod(col, BLOCK)
+        s, bloc = divmod(blk, geo.cw)
+        lane = rloc * geo.cw + bloc
+        tile = rt * geo.nslab + s
     if geo.bits == 3:
         u, within = divmod(cin, 32)
         t, half = divmod(within, 2)

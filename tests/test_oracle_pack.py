@@ -38,6 +38,51 @@ def test_hand_derived_bytes():
     assert int(sec.astype(np.int64).sum()) == 128 + 192 + 1 + 2
 
 
+def test_tile_layout_hand_derived_bytes():
+    c = json.load(open(os.path.join(GOLD, "pack_bytes.json")))["tile_b4"]
+    codes = np.zeros((c["d_out"], c["d_in"]), dtype=np.uint8)
+    for i, j, q in c["sparse_codes"]:
+        codes[i, j] = q
+    geo = packfmt.geometry(c["d_out"], c["d_in"], c["bits"], 0, 0, c["layout"])
+    assert (geo.n_rt, geo.nbp, geo.nblk, geo.d_out_pad) == (1, 1, 2, 32)
+    sec = packfmt.pack_codes(codes, geo)
+    assert sec.size == 32 * 256 * 4 // 8
+    for off, b in c["bytes_at"].items():
+        assert sec[int(off):int(off) + len(b)].tolist() == b
+    assert int(np.count_nonzero(sec)) == 3
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+@pytest.mark.parametrize("d_out,d_in", [(1, 1), (70, 600), (33, 256), (5, 1000)])
+def test_tile_layout_round_trip_and_twin(bits, d_out, d_in):
+    rng = np.random.default_rng(d_out + d_in + bits)
+    codes = rng.integers(0, 1 << bits, size=(d_out, d_in), dtype=np.uint8)
+    geo = packfmt.geometry(d_out, d_in, bits, 0, 0, 1)
+    sec = packfmt.pack_codes(codes, geo)
+    assert sec.size == geo.d_out_pad * geo.nblk * 128 * bits // 8
+    blob = np.zeros(geo.total_bytes, dtype=np.uint8)
+    blob[:sec.size] = sec
+    np.testing.assert_array_equal(packfmt.unpack_codes(blob, geo), codes)
+    if d_out * d_in < 30000:
+        np.testing.assert_array_equal(packfmt.pack_codes_bitwise(codes, geo), sec)
+
+
+def test_tile_layout_blob_sections():
+    L = make_layer(LayerSpec("t", 700, 45, 3, 256, 11, 5))
+    blob, geo = packfmt.pack_layer(L.codes, L.scale, L.zero, 256, L.weak_idx, L.weak_w, 3, layout=1)
+    assert geo.layout == 1 and blob.size == geo.total_bytes
+    for off in (geo.off_sz, geo.off_weak_w, geo.off_weak_idx, geo.off_wmask, geo.off_scratch):
+        assert off % 256 == 0
+    np.testing.assert_array_equal(packfmt.unpack_codes(blob, geo), L.codes)
+    s, z, ix, ww = packfmt.unpack_params(blob, geo)
+    np.testing.assert_array_equal(ix, L.weak_idx)
+    np.testing.assert_array_equal(ww.view(np.uint16), L.weak_w.view(np.uint16))
+    np.testing.assert_array_equal(s.view(np.uint16), L.scale.view(np.uint16))
+    mask = np.unpackbits(blob[geo.off_wmask:geo.off_wmask + geo.nbp * 32], bitorder="little")
+    assert np.flatnonzero(mask).tolist() == L.weak_idx.tolist()
+    assert not blob[geo.off_scratch:].any()
+
+
 @pytest.mark.parametrize("bits", [3, 4])
 @pytest.mark.parametrize("d_out,d_in", [(1, 1), (5, 200), (16, 256), (9, 128 * 7), (64, 128 * 40), (3, 128 * 65)])
 def test_round_trip_and_size(bits, d_out, d_in):
