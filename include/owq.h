@@ -45,7 +45,8 @@ typedef enum {
   OWQ_ERR_BATCH = 8,      /* batch < 0 or above OWQ_MAX_BATCH */
   OWQ_ERR_HANDLE = 9,     /* not a live handle */
   OWQ_ERR_HIP = 10,       /* a HIP call failed; see owq_layer_info_t.last_hip_error */
-  OWQ_ERR_UNSUPPORTED = 11 /* the layer needs more on-chip memory than one workgroup may use */
+  OWQ_ERR_UNSUPPORTED = 11, /* the layer needs more on-chip memory than one workgroup may use */
+  OWQ_ERR_LAYOUT = 12      /* layout is neither OWQ_LAYOUT_GEMV nor OWQ_LAYOUT_TILE */
 } owq_status_t;
 
 #define OWQ_MAX_BATCH 65535
@@ -74,7 +75,18 @@ typedef struct {
   const uint16_t *zero;
   const int32_t *weak_idx;
   const uint16_t *weak_w;
+  int32_t layout;     /* OWQ_LAYOUT_GEMV (0) or OWQ_LAYOUT_TILE (1), see below */
 } owq_layer_desc_t;
+
+/*
+ * Two packed layouts hold the same content.  OWQ_LAYOUT_GEMV is built for single tokens
+ * and small batches (one lane streams 128 columns of one row; batch rows are separate
+ * passes over the weights).  OWQ_LAYOUT_TILE is built for batches (prefill): 32 rows by
+ * 256 columns per tile, unpacked straight into matrix-core operands, 64 tokens per pass
+ * over the weights.  Either layout accepts any batch; they differ in speed only.
+ */
+#define OWQ_LAYOUT_GEMV 0
+#define OWQ_LAYOUT_TILE 1
 
 /*
  * Geometry of the packed blob (format version 1) and the launch shape in use.
@@ -87,7 +99,10 @@ typedef struct {
   int32_t d_out, d_in, bits, group_size, k;
   int32_t nblk, cw, r, nact, nslab, n_rt, d_out_pad, chunks, n_groups, kp;
   uint64_t off_codes, off_sz, off_weak_w, off_weak_idx, total_bytes;
-  /* launch shape of the batch <= 16 path (filled for handles only) */
+  /* tile layout only: block pairs per row, weak-column bit mask, run-time scratch area */
+  int32_t layout, nbp;
+  uint64_t off_wmask, off_scratch;
+  /* launch shape (filled for handles only) */
   int32_t row_tiles_per_wg, row_splits, waves_per_wg, prefetch_depth;
   int32_t workgroups, lds_bytes;
   int32_t last_hip_error;
@@ -138,7 +153,9 @@ owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t
  * Products are accumulated in fp32 and rounded once to fp16 (nearest even).
  * The work is enqueued on stream; the call does not wait, allocate or copy.
  * batch == 0 is a no-op.  The device of dev_buf must be current.
- * Handles are immutable: concurrent calls on different streams are allowed.
+ * Handles of the GEMV layout are immutable: concurrent calls on different streams are
+ * allowed.  A handle of the tile layout keeps intermediate results in the scratch area of
+ * its blob: calls on one such handle must not overlap in time.
  */
 owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream);
 

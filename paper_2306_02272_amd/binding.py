@@ -18,9 +18,11 @@ LIB_PATH = os.path.join(_HERE, "libowq.so")
 OWQ_OK = 0
 STATUS_NAMES = ["OWQ_OK", "OWQ_ERR_NULL", "OWQ_ERR_SHAPE", "OWQ_ERR_BITS", "OWQ_ERR_GROUP",
                 "OWQ_ERR_CODE_RANGE", "OWQ_ERR_INDEX", "OWQ_ERR_BUFFER", "OWQ_ERR_BATCH",
-                "OWQ_ERR_HANDLE", "OWQ_ERR_HIP", "OWQ_ERR_UNSUPPORTED"]
+                "OWQ_ERR_HANDLE", "OWQ_ERR_HIP", "OWQ_ERR_UNSUPPORTED", "OWQ_ERR_LAYOUT"]
 (OWQ_ERR_NULL, OWQ_ERR_SHAPE, OWQ_ERR_BITS, OWQ_ERR_GROUP, OWQ_ERR_CODE_RANGE, OWQ_ERR_INDEX,
- OWQ_ERR_BUFFER, OWQ_ERR_BATCH, OWQ_ERR_HANDLE, OWQ_ERR_HIP, OWQ_ERR_UNSUPPORTED) = range(1, 12)
+ OWQ_ERR_BUFFER, OWQ_ERR_BATCH, OWQ_ERR_HANDLE, OWQ_ERR_HIP, OWQ_ERR_UNSUPPORTED,
+ OWQ_ERR_LAYOUT) = range(1, 13)
+OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE = 0, 1
 
 # every symbol include/owq.h declares
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
@@ -39,7 +41,7 @@ class LayerDesc(C.Structure):
     _fields_ = [("d_out", C.c_int32), ("d_in", C.c_int32), ("bits", C.c_int32),
                 ("group_size", C.c_int32), ("k", C.c_int32),
                 ("codes", C.c_void_p), ("scale", C.c_void_p), ("zero", C.c_void_p),
-                ("weak_idx", C.c_void_p), ("weak_w", C.c_void_p)]
+                ("weak_idx", C.c_void_p), ("weak_w", C.c_void_p), ("layout", C.c_int32)]
 
 
 class LayerInfo(C.Structure):
@@ -48,6 +50,8 @@ class LayerInfo(C.Structure):
                  "nact", "nslab", "n_rt", "d_out_pad", "chunks", "n_groups", "kp")] + \
                [(n, C.c_uint64) for n in
                 ("off_codes", "off_sz", "off_weak_w", "off_weak_idx", "total_bytes")] + \
+               [("layout", C.c_int32), ("nbp", C.c_int32), ("off_wmask", C.c_uint64),
+                ("off_scratch", C.c_uint64)] + \
                [(n, C.c_int32) for n in
                 ("row_tiles_per_wg", "row_splits", "waves_per_wg", "prefetch_depth", "workgroups",
                  "lds_bytes", "last_hip_error", "reserved")]
@@ -97,7 +101,7 @@ def _ptr(a):
 
 
 def make_desc(d_out, d_in, bits, group_size, k, codes=None, scale=None, zero=None,
-              weak_idx=None, weak_w=None):
+              weak_idx=None, weak_w=None, layout=0):
     """LayerDesc over numpy arrays (kept alive on the returned object)."""
     def prep(a, dt):
         if a is None:
@@ -109,15 +113,15 @@ def make_desc(d_out, d_in, bits, group_size, k, codes=None, scale=None, zero=Non
         return a
     keep = [prep(codes, np.uint8), prep(scale, np.uint16), prep(zero, np.uint16),
             prep(weak_idx, np.int32), prep(weak_w, np.uint16)]
-    d = LayerDesc(d_out, d_in, bits, group_size, k, *[_ptr(a) for a in keep])
+    d = LayerDesc(d_out, d_in, bits, group_size, k, *[_ptr(a) for a in keep], layout)
     d._keep = keep
     return d
 
 
-def desc_from_layer(layer):
+def desc_from_layer(layer, layout=0):
     """LayerDesc for a synth.Layer-like object (numpy fields)."""
     return make_desc(layer.d_out, layer.d_in, layer.bits, layer.group_size, layer.k,
-                     layer.codes, layer.scale, layer.zero, layer.weak_idx, layer.weak_w)
+                     layer.codes, layer.scale, layer.zero, layer.weak_idx, layer.weak_w, layout)
 
 
 def owq_geometry(desc) -> LayerInfo:
@@ -194,12 +198,12 @@ def owq_status_str(status: int) -> str:
 class OwqLinear:
     """A packed layer resident on the current GPU (torch owns the memory, nothing else)."""
 
-    def __init__(self, layer, device="cuda", packed=None):
+    def __init__(self, layer, device="cuda", packed=None, layout=0):
         """Pack `layer` onto the GPU; with `packed` (a uint8 CUDA tensor holding a blob of the
         same shape) only a handle is opened over a private copy of it."""
         import torch
         self.torch = torch
-        self.desc = desc_from_layer(layer)
+        self.desc = desc_from_layer(layer, layout)
         nbytes = owq_packed_bytes(self.desc)
         if packed is None:
             self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)

@@ -14,13 +14,13 @@ extern "C" {
 
 owq_status_t owq_geometry(const owq_layer_desc_t *desc, owq_layer_info_t *info) {
   if (!desc || !info) return OWQ_ERR_NULL;
-  return compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, info);
+  return compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, info);
 }
 
 owq_status_t owq_packed_bytes(const owq_layer_desc_t *desc, size_t *bytes) {
   if (!desc || !bytes) return OWQ_ERR_NULL;
   owq_layer_info_t g;
-  owq_status_t st = compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  owq_status_t st = compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, &g);
   if (st != OWQ_OK) return st;
   *bytes = (size_t)g.total_bytes;
   return OWQ_OK;
@@ -31,7 +31,7 @@ owq_status_t owq_pack_host(const owq_layer_desc_t *desc, void *host_buf, size_t 
   owq_status_t st = validate_desc(desc);
   if (st != OWQ_OK) return st;
   owq_layer_info_t g;
-  compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, &g);
   if (bytes < g.total_bytes) return OWQ_ERR_BUFFER;
   pack_blob(desc, g, static_cast<uint8_t *>(host_buf));
   return OWQ_OK;
@@ -40,15 +40,25 @@ owq_status_t owq_pack_host(const owq_layer_desc_t *desc, void *host_buf, size_t 
 owq_status_t owq_unpack_codes(const void *host_packed, const owq_layer_info_t *info, uint8_t *codes) {
   if (!host_packed || !info || !codes) return OWQ_ERR_NULL;
   owq_layer_info_t g;
-  owq_status_t st = compute_geometry(info->d_out, info->d_in, info->bits, info->group_size, info->k, &g);
+  owq_status_t st = compute_geometry(info->d_out, info->d_in, info->bits, info->group_size, info->k, info->layout, &g);
   if (st != OWQ_OK) return st;
   const uint32_t *dwords = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(host_packed) + g.off_codes);
   for (int32_t row = 0; row < g.d_out; ++row) {
     const int32_t rt = row / g.r, rloc = row % g.r;
     for (int32_t j = 0; j < g.d_in; ++j) {
-      const int32_t blk = j / kBlockCols, cin = j % kBlockCols;
-      const int64_t tile = (int64_t)rt * g.nslab + blk / g.cw;
-      const int32_t lane = rloc * g.cw + blk % g.cw;
+      int32_t cin, lane;
+      int64_t tile;
+      if (g.layout == OWQ_LAYOUT_TILE) {
+        const int32_t c256 = j % 256, c128 = c256 % 128, c16 = c128 % 16;
+        cin = 64 * (c256 / 128) + 8 * (c128 / 16) + c16 % 8;
+        lane = (c16 / 8) * kTileRows + rloc;
+        tile = (int64_t)rt * g.nbp + j / 256;
+      } else {
+        const int32_t blk = j / kBlockCols;
+        cin = j % kBlockCols;
+        tile = (int64_t)rt * g.nslab + blk / g.cw;
+        lane = rloc * g.cw + blk % g.cw;
+      }
       int v, bit;          // dword of the lane, bit inside its 16-bit half
       uint32_t code = 0;
       const int half = cin & 1;
@@ -103,7 +113,7 @@ owq_status_t owq_pack_layer(const owq_layer_desc_t *desc, void *dev_buf, size_t 
   owq_status_t st = validate_desc(desc);
   if (st != OWQ_OK) return st;
   owq_layer_info_t g;
-  compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, &g);
   if (dev_bytes < g.total_bytes) return OWQ_ERR_BUFFER;
   if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign != 0) return OWQ_ERR_BUFFER;
 
@@ -124,7 +134,7 @@ owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t
   if (!desc || !dev_buf || !out) return OWQ_ERR_NULL;
   *out = nullptr;
   owq_layer_info_t g;
-  owq_status_t st = compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, &g);
+  owq_status_t st = compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, &g);
   if (st != OWQ_OK) return st;
   if (dev_bytes < g.total_bytes) return OWQ_ERR_BUFFER;
   if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign != 0) return OWQ_ERR_BUFFER;
@@ -208,6 +218,7 @@ const char *owq_status_str(owq_status_t s) {
     case OWQ_ERR_HANDLE: return "not a live handle";
     case OWQ_ERR_HIP: return "HIP call failed";
     case OWQ_ERR_UNSUPPORTED: return "layer too large for one workgroup's on-chip memory";
+    case OWQ_ERR_LAYOUT: return "unknown layout";
   }
   return "unknown status";
 }

@@ -14,7 +14,11 @@ constexpr uint32_t kMagic = 0x4f575131u;  // "OWQ1"
 
 // Shape checks + geometry of the packed blob.  Fills every geometry field of info.
 owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t group_size,
-                              int32_t k, owq_layer_info_t *info);
+                              int32_t k, int32_t layout, owq_layer_info_t *info);
+
+constexpr int kTileRows = 32;        // rows per tile of the tile layout
+constexpr int kScratchBatch = 64;    // tokens per pass of the tile path
+constexpr int kScratchSplits = 8;    // most column splits whose partial results the scratch area holds
 
 // Full validation of a description (pointers, code range, index order).
 owq_status_t validate_desc(const owq_layer_desc_t *desc);

@@ -17,14 +17,39 @@ namespace owq {
 static inline uint64_t align_up(uint64_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
 owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t group_size,
-                              int32_t k, owq_layer_info_t *g) {
+                              int32_t k, int32_t layout, owq_layer_info_t *g) {
   if (d_out < 1 || d_in < 1) return OWQ_ERR_SHAPE;
   if (bits != 3 && bits != 4) return OWQ_ERR_BITS;
   if (group_size < 0 || (group_size != 0 && group_size % kBlockCols != 0)) return OWQ_ERR_GROUP;
   if (k < 0 || k > d_in) return OWQ_ERR_INDEX;
+  if (layout != OWQ_LAYOUT_GEMV && layout != OWQ_LAYOUT_TILE) return OWQ_ERR_LAYOUT;
   std::memset(g, 0, sizeof(*g));
   g->format_version = OWQ_FORMAT_VERSION;
   g->d_out = d_out; g->d_in = d_in; g->bits = bits; g->group_size = group_size; g->k = k;
+  g->layout = layout;
+  if (layout == OWQ_LAYOUT_TILE) {
+    // 32 rows x one pair of blocks per tile; lane = (half of the pair's columns, row).
+    g->nbp = (d_in + 2 * kBlockCols - 1) / (2 * kBlockCols);
+    g->nblk = 2 * g->nbp;
+    g->cw = 1; g->r = kTileRows; g->nact = 64; g->nslab = g->nbp;
+    g->n_rt = (d_out + kTileRows - 1) / kTileRows;
+    g->d_out_pad = g->n_rt * kTileRows;
+    g->chunks = bits == 3 ? 3 : 4;
+    g->n_groups = group_size == 0 ? 1 : (d_in + group_size - 1) / group_size;
+    g->kp = (k + 7) / 8 * 8;
+    g->off_codes = 0;
+    g->off_sz = align_up((uint64_t)g->n_rt * g->nbp * 64 * g->chunks * 16);
+    g->off_weak_w = align_up(g->off_sz + (uint64_t)g->d_out_pad * g->n_groups * 4);
+    g->off_weak_idx = align_up(g->off_weak_w + (uint64_t)g->d_out_pad * g->kp * 2);
+    g->off_wmask = align_up(g->off_weak_idx + (uint64_t)g->kp * 4);
+    g->off_scratch = align_up(g->off_wmask + (uint64_t)g->nbp * 32);
+    const uint64_t scratch = (uint64_t)kScratchBatch * g->nbp * 256 * 2 + (uint64_t)g->nblk * kScratchBatch * 8 +
+                             (uint64_t)kScratchBatch * g->kp * 2 +
+                             (uint64_t)kScratchSplits * kScratchBatch * g->d_out_pad * 4;
+    g->total_bytes = align_up(g->off_scratch + scratch);
+    if (g->total_bytes >= (1ull << 32)) return OWQ_ERR_SHAPE;
+    return OWQ_OK;
+  }
   g->nblk = (d_in + kBlockCols - 1) / kBlockCols;
   // Tile width: as many blocks of a row side by side as the wave can hold while
   // keeping at least 60 of its 64 lanes busy.
@@ -54,7 +79,7 @@ owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t
 owq_status_t validate_desc(const owq_layer_desc_t *d) {
   if (!d) return OWQ_ERR_NULL;
   owq_layer_info_t g;
-  owq_status_t st = compute_geometry(d->d_out, d->d_in, d->bits, d->group_size, d->k, &g);
+  owq_status_t st = compute_geometry(d->d_out, d->d_in, d->bits, d->group_size, d->k, d->layout, &g);
   if (st != OWQ_OK) return st;
   if (!d->codes || !d->scale || !d->zero) return OWQ_ERR_NULL;
   if (d->k > 0 && (!d->weak_idx || !d->weak_w)) return OWQ_ERR_NULL;
@@ -111,6 +136,32 @@ void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *ou
   uint8_t q[kBlockCols];
   uint32_t dw[16];
   const int ndw = g.chunks * 4;
+  if (g.layout == OWQ_LAYOUT_TILE) {
+    for (int32_t row = 0; row < g.d_out; ++row) {
+      const int32_t rt = row / kTileRows, rloc = row % kTileRows;
+      const uint8_t *src = d->codes + (int64_t)row * d->d_in;
+      for (int32_t bp = 0; bp < g.nbp; ++bp)
+        for (int kg = 0; kg < 2; ++kg) {
+          // the lane's 128 codes: for both blocks of the pair, 8 octets at stride 16
+          for (int b = 0; b < 2; ++b)
+            for (int t = 0; t < 8; ++t)
+              for (int e = 0; e < 8; ++e) {
+                const int32_t j = bp * 256 + b * 128 + t * 16 + kg * 8 + e;
+                q[b * 64 + t * 8 + e] = (j < d->d_in && !weak[j]) ? src[j] : 0;
+              }
+          block_to_dwords(q, g.bits, dw);
+          const int64_t tile = (int64_t)rt * g.nbp + bp;
+          const int32_t lane = kg * kTileRows + rloc;
+          for (int v = 0; v < ndw; ++v) {
+            const int64_t unit = (tile * g.chunks + v / 4) * 64 + lane;
+            codes[unit * 4 + (v & 3)] = dw[v];
+          }
+        }
+    }
+    uint8_t *wm = out + g.off_wmask;
+    for (int32_t j = 0; j < d->d_in; ++j)
+      if (weak[j]) wm[j >> 3] |= (uint8_t)(1u << (j & 7));
+  } else
   for (int32_t row = 0; row < g.d_out; ++row) {
     const int32_t rt = row / g.r, rloc = row % g.r;
     const uint8_t *src = d->codes + (int64_t)row * d->d_in;

@@ -32,9 +32,10 @@ def test_exports_match_header(lib):
 
 
 def test_struct_sizes_match_header(lib):
-    # 16 + 8 int32 and 5 uint64 in the info record; 5 int32 (+pad) and 5 pointers in the description
-    assert C.sizeof(B.LayerInfo) == 16 * 4 + 5 * 8 + 8 * 4
-    assert C.sizeof(B.LayerDesc) == 24 + 5 * 8
+    # 16 + 2 + 8 int32 and 5 + 2 uint64 in the info record; 5 int32 (+pad), 5 pointers and one
+    # int32 (+pad) in the description
+    assert C.sizeof(B.LayerInfo) == 26 * 4 + 7 * 8
+    assert C.sizeof(B.LayerDesc) == 24 + 5 * 8 + 8
 
 
 @pytest.mark.parametrize("spec", [
@@ -57,6 +58,25 @@ def test_host_pack_equals_oracle_pack(lib, spec):
     np.testing.assert_array_equal(blob, want)
     np.testing.assert_array_equal(B.owq_unpack_codes(blob, info), L.codes)
     np.testing.assert_array_equal(packfmt.unpack_codes(blob, geo), L.codes)
+
+
+@pytest.mark.parametrize("spec", [
+    LayerSpec("ta", 700, 45, 3, 256, 11, 21), LayerSpec("tb", 256, 32, 4, 0, 0, 22),
+    LayerSpec("tc", 1000, 70, 4, 128, 9, 23), LayerSpec("td", 130, 3, 3, 0, 130, 24)])
+def test_tile_layout_host_pack_equals_oracle_pack(lib, spec):
+    L = make_layer(spec)
+    d = B.desc_from_layer(L, B.OWQ_LAYOUT_TILE)
+    blob = B.owq_pack_host(d)
+    want, geo = packfmt.pack_layer(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, L.weak_w, L.bits,
+                                   layout=1)
+    info = B.owq_geometry(d)
+    for f in ("layout", "nbp", "nblk", "n_rt", "d_out_pad", "chunks", "n_groups", "kp", "off_codes", "off_sz",
+              "off_weak_w", "off_weak_idx", "off_wmask", "off_scratch", "total_bytes"):
+        assert getattr(info, f) == getattr(geo, f), f
+    np.testing.assert_array_equal(blob, want)
+    np.testing.assert_array_equal(B.owq_unpack_codes(blob, info), L.codes)
+    bad = B.desc_from_layer(L, 7)
+    assert _status(B.owq_packed_bytes, bad) == B.OWQ_ERR_LAYOUT
 
 
 def _status(fn, *a):
@@ -113,6 +133,6 @@ def test_dead_handles_are_refused(lib):
 
 
 def test_status_strings(lib):
-    seen = {B.owq_status_str(s) for s in range(12)}
-    assert len(seen) == 12 and "ok" in seen
+    seen = {B.owq_status_str(s) for s in range(13)}
+    assert len(seen) == 13 and "ok" in seen
     assert B.owq_status_str(99) == "unknown status"
