@@ -53,7 +53,10 @@ with these differences:
   * two more sections follow weak_idx: wmask, one byte per 8 input columns
     (bit e = column 8i+e is weak), nbp*32 bytes; and a scratch area the library
     uses at run time (contents undefined, zero in a fresh blob) of
-    64*(nbp*256)*2 + nblk*64*8 + 64*kp*2 + 8*64*(n_rt*32)*4 bytes.
+    64*(nbp*256)*2 + nblk*64*8 + 16384 + 64*kp*2 + (min(512, n_rg*nbp) + 2*n_rg)*65536
+    bytes, n_rg = ceil(n_rt / 8): staged activations of 64 tokens, their sums per block
+    and per column chunk, the activations at the weak columns, and fp32 partial results
+    of 256 rows by 64 tokens each.
 """
 from __future__ import annotations
 
@@ -107,7 +110,8 @@ def tile_shape(nblk: int):
 
 TILE_ROWS = 32
 SCRATCH_BATCH = 64
-SCRATCH_SPLITS = 8
+SCRATCH_GRID = 512          # most workgroups of the batched kernel
+SCRATCH_SLOT = 65536        # bytes of one partial result: 256 rows x 64 tokens, fp32
 
 
 def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int, layout: int = 0) -> Geometry:
@@ -126,8 +130,9 @@ def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int, layout: 
         off_weak_idx = _align(off_weak_w + d_out_pad * kp * 2)
         off_wmask = _align(off_weak_idx + kp * 4)
         off_scratch = _align(off_wmask + nbp * 32)
-        scratch = (SCRATCH_BATCH * nbp * 256 * 2 + nblk * SCRATCH_BATCH * 8 + SCRATCH_BATCH * kp * 2
-                   + SCRATCH_SPLITS * SCRATCH_BATCH * d_out_pad * 4)
+        n_rg = -(-n_rt // 8)
+        scratch = (SCRATCH_BATCH * nbp * 256 * 2 + nblk * SCRATCH_BATCH * 8 + 16384 + SCRATCH_BATCH * kp * 2
+                   + (min(SCRATCH_GRID, n_rg * nbp) + 2 * n_rg) * SCRATCH_SLOT)
         total = _align(off_scratch + scratch)
         return Geometry(d_out, d_in, bits, group_size, k, nblk, 1, TILE_ROWS, 64, nbp, n_rt,
                         d_out_pad, chunks, n_groups, kp, 0, off_sz, off_weak_w, off_weak_idx,

@@ -86,14 +86,22 @@ owq_status_t owq_unpack_codes(const void *host_packed, const owq_layer_info_t *i
 static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_handle_t *out) {
   int32_t lds_limit = 0;
   if (device_lds_limit(&lds_limit) != 0) return OWQ_ERR_HIP;
-  LaunchShape shape = default_shape(g, lds_limit);
-  if (shape.rtw < 1) return OWQ_ERR_UNSUPPORTED;
-  if (prepare_kernels(lds_limit) != 0) return OWQ_ERR_HIP;
+  LaunchShape shape{};
+  int32_t tile_grid = 0;
+  if (g.layout == OWQ_LAYOUT_TILE) {
+    if (lds_limit < 65536) return OWQ_ERR_UNSUPPORTED;
+    tile_grid = tile_scratch(g).grid_max;
+  } else {
+    shape = default_shape(g, lds_limit);
+    if (shape.rtw < 1) return OWQ_ERR_UNSUPPORTED;
+    if (prepare_kernels(lds_limit) != 0) return OWQ_ERR_HIP;
+  }
   owq_layer_s *h = new (std::nothrow) owq_layer_s;
   if (!h) return OWQ_ERR_BUFFER;
   h->magic = kMagic;
   h->info = g;
   h->shape = shape;
+  h->tile_grid = tile_grid;
   h->dev_buf = dev_buf;
   h->lds_limit = lds_limit;
   const uint8_t *base = static_cast<const uint8_t *>(dev_buf);
@@ -147,7 +155,9 @@ owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, v
   if (batch == 0) return OWQ_OK;
   if (!x || !y) return OWQ_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(x) % 2 != 0 || reinterpret_cast<uintptr_t>(y) % 2 != 0) return OWQ_ERR_BUFFER;
-  const int herr = launch_gemv(h->info, h->shape, h->dev, x, y, batch, stream);
+  const int herr = h->info.layout == OWQ_LAYOUT_TILE
+                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, x, y, batch, stream)
+                       : launch_gemv(h->info, h->shape, h->dev, x, y, batch, stream);
   if (herr != 0) {
     h->info.last_hip_error = herr;
     return OWQ_ERR_HIP;
@@ -170,8 +180,8 @@ owq_status_t owq_layer_info(owq_handle_t h, owq_layer_info_t *info) {
   info->row_splits = h->shape.rsplit;
   info->waves_per_wg = h->shape.waves;
   info->prefetch_depth = h->shape.depth;
-  info->workgroups = h->shape.nwg;
-  info->lds_bytes = h->shape.lds_bytes;
+  info->workgroups = h->info.layout == OWQ_LAYOUT_TILE ? h->tile_grid : h->shape.nwg;
+  info->lds_bytes = h->info.layout == OWQ_LAYOUT_TILE ? 65536 : h->shape.lds_bytes;
   return OWQ_OK;
 }
 
@@ -189,6 +199,13 @@ owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes) {
 
 owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t waves, int32_t depth) {
   if (!live(h)) return OWQ_ERR_HANDLE;
+  if (h->info.layout == OWQ_LAYOUT_TILE) {
+    // tile layout: the first argument is the number of workgroups of the main kernel
+    if (rsplit || waves || depth) return OWQ_ERR_SHAPE;
+    if (rtw < 0 || rtw > tile_scratch(h->info).grid_max) return OWQ_ERR_SHAPE;
+    if (rtw) h->tile_grid = rtw;
+    return OWQ_OK;
+  }
   LaunchShape s = h->shape;
   if (rtw) s.rtw = rtw;
   if (rsplit) s.rsplit = rsplit;

@@ -18,7 +18,23 @@ owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t
 
 constexpr int kTileRows = 32;        // rows per tile of the tile layout
 constexpr int kScratchBatch = 64;    // tokens per pass of the tile path
-constexpr int kScratchSplits = 8;    // most column splits whose partial results the scratch area holds
+constexpr int kTileGroupTiles = 8;   // row tiles per row group (one workgroup: 4 waves x 2 tiles)
+constexpr int kTileGridMax = 512;    // most workgroups of the tile kernel
+constexpr int kTileSlotBytes = 65536;  // one partial result: 256 rows x 64 tokens, fp32
+constexpr int kTileChunksMax = 32;   // most column chunks of the staging kernel
+
+// Map of the scratch area of a tile-layout blob (byte offsets from off_scratch).
+struct TileScratch {
+  int32_t n_rg;          // row groups of 256 rows
+  int32_t grid_max;      // most workgroups the partial slots allow: min(kTileGridMax, n_rg * nbp)
+  uint64_t off_xs;       // staged activations: [nbp][16 k-steps][2 token tiles][64 lanes][8 fp16]
+  uint64_t off_bsum;     // [64 tokens][nblk] (sum x, sum c*x) as two floats
+  uint64_t off_csum;     // [64 tokens][kTileChunksMax] the same per column chunk
+  uint64_t off_xw;       // [64 tokens][kp] fp16: activations at the weak columns
+  uint64_t off_slots;    // partial results: grid_max + n_rg dense slots, then n_rg weak slots
+  uint64_t total;
+};
+TileScratch tile_scratch(const owq_layer_info_t &g);
 
 // Full validation of a description (pointers, code range, index order).
 owq_status_t validate_desc(const owq_layer_desc_t *desc);
@@ -53,6 +69,11 @@ struct DeviceLayer {
 int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev,
                 const void *x, void *y, int32_t batch, void *stream);
 int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when needed
+
+// Tile path (defined in owq_tile.hip): three launches per pass of up to 64 tokens.
+// blob = DEVICE address of the packed blob; grid = workgroups of the main kernel.
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void *x, void *y,
+                int32_t batch, void *stream);
 int device_lds_limit(int32_t *bytes);
 
 }  // namespace owq
@@ -64,4 +85,5 @@ struct owq_layer_s {
   owq::DeviceLayer dev;
   void *dev_buf;
   int32_t lds_limit;
+  int32_t tile_grid;     // workgroups of the tile kernel (tile layout only)
 };

@@ -16,6 +16,20 @@ namespace owq {
 
 static inline uint64_t align_up(uint64_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
+TileScratch tile_scratch(const owq_layer_info_t &g) {
+  TileScratch t{};
+  t.n_rg = (g.n_rt + kTileGroupTiles - 1) / kTileGroupTiles;
+  const int64_t steps = (int64_t)t.n_rg * g.nbp;
+  t.grid_max = steps < kTileGridMax ? (int32_t)steps : kTileGridMax;
+  t.off_xs = 0;
+  t.off_bsum = t.off_xs + (uint64_t)kScratchBatch * g.nbp * 256 * 2;
+  t.off_csum = t.off_bsum + (uint64_t)g.nblk * kScratchBatch * 8;
+  t.off_xw = t.off_csum + (uint64_t)kScratchBatch * kTileChunksMax * 8;
+  t.off_slots = t.off_xw + (uint64_t)kScratchBatch * g.kp * 2;
+  t.total = t.off_slots + (uint64_t)(t.grid_max + 2 * t.n_rg) * kTileSlotBytes;
+  return t;
+}
+
 owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t group_size,
                               int32_t k, int32_t layout, owq_layer_info_t *g) {
   if (d_out < 1 || d_in < 1) return OWQ_ERR_SHAPE;
@@ -43,9 +57,8 @@ owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t
     g->off_weak_idx = align_up(g->off_weak_w + (uint64_t)g->d_out_pad * g->kp * 2);
     g->off_wmask = align_up(g->off_weak_idx + (uint64_t)g->kp * 4);
     g->off_scratch = align_up(g->off_wmask + (uint64_t)g->nbp * 32);
-    const uint64_t scratch = (uint64_t)kScratchBatch * g->nbp * 256 * 2 + (uint64_t)g->nblk * kScratchBatch * 8 +
-                             (uint64_t)kScratchBatch * g->kp * 2 +
-                             (uint64_t)kScratchSplits * kScratchBatch * g->d_out_pad * 4;
+    const TileScratch ts = tile_scratch(*g);
+    const uint64_t scratch = ts.total;
     g->total_bytes = align_up(g->off_scratch + scratch);
     if (g->total_bytes >= (1ull << 32)) return OWQ_ERR_SHAPE;
     return OWQ_OK;

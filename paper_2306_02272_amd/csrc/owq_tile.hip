@@ -1,0 +1,575 @@
+// Batched path of the OWQ mixed-precision linear layer on the matrix cores of gfx950
+// (tile layout: 32 rows x 256 columns per tile, 64 tokens per pass over the weights).
+//
+// Same result as the single-token kernel (paper: storage paragraph of "Outlier-Aware
+// Weight Quantization", section "Acceleration on Real Device"):
+//     y[n,i] = sum_{j not weak} s_ig (q_ij - z_ig) x[n,j]  +  sum_t Ww_it x[n, idx_t]
+// computed as a dense contraction.  The paper measures single tokens only; this path is
+// this library's own extension for prompts.
+//
+// Three launches per pass of up to 64 tokens:
+//   stage   copies x into the order the matrix instruction reads it, clears the weak
+//           columns (by select), gathers x at the weak indices and sums, per token and
+//           block, x and c*x (c = the constant each code is OR-ed into, see below);
+//   mma     every wave owns 64 rows x 64 tokens of fp32 accumulators and walks along the
+//           columns: codes go from registers straight into the A operand (a pair of codes
+//           is masked out of a dword and OR-ed into the mantissas of 2^(10-o), giving
+//           2^(10-o)+q exactly), tokens come from LDS as the B operand.  The flattened
+//           (row group, column step) sequence is cut into equal ranges, one per workgroup,
+//           so that all compute units stay busy whatever the shape; a workgroup writes one
+//           partial result per row group it touches.  The fp16 weak columns are further
+//           K-steps whose result goes to a slot of its own (it must not be scaled);
+//   finish  adds the partial results of a row group in a fixed order, removes the constant
+//           part and the zero point, scales, adds the weak product, rounds to fp16.
+// No atomics: results are reproducible.
+#include <hip/hip_runtime.h>
+
+#include "owq_device.h"
+#include "owq_internal.h"
+
+namespace owq {
+
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef float f16_t __attribute__((ext_vector_type(16)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+typedef float f2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kUnitsPerTile = 2048;   // 16-byte units of one staged activation tile (256 columns x 64 tokens)
+constexpr int kSlotUnits = kTileSlotBytes / 16;
+
+// Bit offset o of pair i (columns 2i, 2i+1) of octet t of a block inside its 16-bit window;
+// the pair is OR-ed into 2^(10-o).  3-bit: the octet's place in its quad of 32 codes decides.
+__device__ __forceinline__ constexpr int pair_offset(int bits, int t, int i) {
+  constexpr int off3[4][4] = {{0, 3, 6, 1}, {4, 7, 2, 5}, {0, 3, 6, 1}, {4, 7, 4, 7}};
+  constexpr int off4[4] = {0, 4, 2, 6};
+  return bits == 3 ? off3[t & 3][i] : off4[i];
+}
+
+// ---------------------------------------------------------------------------
+// stage
+// ---------------------------------------------------------------------------
+struct StageArgs {
+  const _Float16 *x;           // [ntok][d_in] of this pass
+  const unsigned char *wmask;  // bit e of byte i: column 8i+e is weak
+  const int *weak_idx;         // [kp], padding -1
+  u32x4 *xs;                   // [nbp][16][2][64] units
+  f2_t *bsum;                  // [64][nblk]
+  f2_t *csum;                  // [64][kTileChunksMax]
+  _Float16 *xw;                // [64][kp]
+  int d_in, ntok, nbp, nblk, kp, nchunk;
+};
+
+// grid (column chunk, token tile of 32); thread = (token, one of 8 octets per trip).
+template <int BITS>
+__global__ __launch_bounds__(256) void owq_tile_stage(const StageArgs a) {
+  __shared__ f2_t red[8][2][32];
+  __shared__ f2_t ctot[2][32];
+  const int tid = threadIdx.x, nl = tid & 31, oo = tid >> 5;
+  const int c = blockIdx.x, nt = blockIdx.y;
+  const int n = nt * 32 + nl;
+  const bool valid = n < a.ntok;
+  const int bp0 = (int)((long long)c * a.nbp / a.nchunk), bp1 = (int)((long long)(c + 1) * a.nbp / a.nchunk);
+  const _Float16 *xr = a.x + (size_t)(valid ? n : 0) * a.d_in;
+  const bool vec = ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((a.d_in & 7) == 0);
+  // octet o = 8*trip + oo of the pair: k-step (o >> 1) & 7, whose place in its quad is (oo >> 1) & 3
+  float cst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (((oo >> 1) & 3) == q) v = (float)(1 << (10 - pair_offset(BITS, q, i)));
+    cst[i] = v;
+  }
+  float cx = 0.f, cb = 0.f;
+  for (int bp = bp0; bp < bp1; ++bp) {
+    float X[2] = {0.f, 0.f}, Bc[2] = {0.f, 0.f};
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int o = it * 8 + oo;
+      const int j0 = bp * 256 + o * 8;
+      u32 w[4] = {0u, 0u, 0u, 0u};
+      if (valid && j0 < a.d_in) {
+        if (vec) {
+          const u32x4 v = *reinterpret_cast<const u32x4 *>(xr + j0);
+          w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+        } else {
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            const int j = j0 + t;
+            const u32 h = j < a.d_in ? (u32)__builtin_bit_cast(unsigned short, xr[j]) : 0u;
+            w[t >> 1] |= h << (16 * (t & 1));
+          }
+        }
+      }
+      const u32 m = a.wmask[bp * 32 + o];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {        // weak columns contribute nothing to the dense term
+        if (m & (1u << (2 * i))) w[i] &= 0xffff0000u;
+        if (m & (2u << (2 * i))) w[i] &= 0x0000ffffu;
+      }
+      if (valid) {
+        const u32x4 v = {w[0], w[1], w[2], w[3]};
+        a.xs[((size_t)(bp * 16 + (o >> 1)) * 2 + nt) * 64 + (o & 1) * 32 + nl] = v;
+      }
+      float sx = 0.f, sb = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float pr = dot2(w[i], kOnes, 0.f);
+        sx += pr;
+        sb = __builtin_fmaf(pr, cst[i], sb);
+      }
+      X[it >> 1] += sx;
+      Bc[it >> 1] += sb;
+    }
+    red[oo][0][nl] = (f2_t){X[0], Bc[0]};
+    red[oo][1][nl] = (f2_t){X[1], Bc[1]};
+    __syncthreads();
+    if (tid < 64) {
+      const int b = tid >> 5;
+      float sx = 0.f, sb = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const f2_t r = red[q][b][nl];
+        sx += r.x;
+        sb += r.y;
+      }
+      if (valid) a.bsum[(size_t)n * a.nblk + 2 * bp + b] = (f2_t){sx, sb};
+      cx += sx;
+      cb += sb;
+    }
+    __syncthreads();
+  }
+  if (tid < 64) ctot[tid >> 5][nl] = (f2_t){cx, cb};
+  __syncthreads();
+  if (tid < 32 && valid) {
+    const f2_t u = ctot[0][nl], v = ctot[1][nl];
+    a.csum[n * kTileChunksMax + c] = (f2_t){u.x + v.x, u.y + v.y};
+  }
+  if (c == 0) {
+    for (int e = tid; e < 32 * a.kp; e += 256) {
+      const int ln = e / a.kp, t = e - ln * a.kp, nn = nt * 32 + ln;
+      if (nn < a.ntok) {
+        const int j = a.weak_idx[t];
+        a.xw[nn * a.kp + t] = j >= 0 ? a.x[(size_t)nn * a.d_in + j] : (_Float16)0;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// mma
+// ---------------------------------------------------------------------------
+struct TileArgs {
+  const u32x4 *codes;
+  const u32 *sz;
+  const u32x4 *weak_w;   // [d_out_pad][kp/8] units
+  const u32x4 *xs;
+  const f2_t *bsum;
+  const u32x4 *xw;       // [64][kp/8] units
+  f4_t *slots;
+  int nbp, n_rt, n_groups, bpg, nblk, kp;
+  int steps;             // row groups x column steps
+  int weak_slot0;        // first weak slot
+};
+
+// A operand of k-step S (16 columns) from the lane's dwords: four packed pairs 2^(10-o)+q.
+template <int BITS, int S>
+__device__ __forceinline__ h8_t a_operand(const u32 *wd, const Magic &M) {
+  u32 r0, r1, r2, r3;
+  if (BITS == 3) {
+    constexpr int u = S >> 2, o = S & 3;
+    const u32 d0 = wd[3 * u], d1 = wd[3 * u + 1], d2 = wd[3 * u + 2];
+    if (o == 0) {
+      const u32 w1 = __builtin_amdgcn_perm(d1, d0, 0x06030401u);
+      r0 = andor(d0, field(3, 0), M.m[0]); r1 = andor(d0, field(3, 3), M.m[3]);
+      r2 = andor(d0, field(3, 6), M.m[6]); r3 = andor(w1, field(3, 1), M.m[1]);
+    } else if (o == 1) {
+      const u32 w1 = __builtin_amdgcn_perm(d1, d0, 0x06030401u);
+      r0 = andor(w1, field(3, 4), M.m[4]); r1 = andor(w1, field(3, 7), M.m[7]);
+      r2 = andor(d1, field(3, 2), M.m[2]); r3 = andor(d1, field(3, 5), M.m[5]);
+    } else if (o == 2) {
+      const u32 w3 = __builtin_amdgcn_perm(d2, d1, 0x06030401u);
+      r0 = andor(w3, field(3, 0), M.m[0]); r1 = andor(w3, field(3, 3), M.m[3]);
+      r2 = andor(w3, field(3, 6), M.m[6]); r3 = andor(d2, field(3, 1), M.m[1]);
+    } else {
+      const u32 w5 = d2 >> 6;
+      r0 = andor(d2, field(3, 4), M.m[4]); r1 = andor(d2, field(3, 7), M.m[7]);
+      r2 = andor(w5, field(3, 4), M.m[4]); r3 = andor(w5, field(3, 7), M.m[7]);
+    }
+  } else {
+    const u32 d = wd[S], w = d >> 6;
+    r0 = andor(d, field(4, 0), M.m[0]); r1 = andor(d, field(4, 4), M.m[4]);
+    r2 = andor(w, field(4, 2), M.m[2]); r3 = andor(w, field(4, 6), M.m[6]);
+  }
+  const u32x4 v = {r0, r1, r2, r3};
+  return __builtin_bit_cast(h8_t, v);
+}
+
+__device__ __forceinline__ f16_t mma(h8_t a, h8_t b, f16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+template <int BITS, int NT, bool GROUPED, int S>
+struct KSteps {
+  // k-steps S..15 of one column step: wd0/wd1 = the dwords of the wave's two row tiles
+  template <typename Epi>
+  static __device__ __forceinline__ void run(const u32 *wd0, const u32 *wd1, const u32x4 *xb, int lane,
+                                             const Magic &M, f16_t *acc, Epi &epi) {
+    const h8_t a0 = a_operand<BITS, S>(wd0, M), a1 = a_operand<BITS, S>(wd1, M);
+    const h8_t b0 = __builtin_bit_cast(h8_t, xb[(S * 2 + 0) * 64 + lane]);
+    acc[0] = mma(a0, b0, acc[0]);
+    acc[2] = mma(a1, b0, acc[2]);
+    if (NT == 2) {
+      const h8_t b1 = __builtin_bit_cast(h8_t, xb[(S * 2 + 1) * 64 + lane]);
+      acc[1] = mma(a0, b1, acc[1]);
+      acc[3] = mma(a1, b1, acc[3]);
+    }
+    if (GROUPED && (S == 7 || S == 15)) epi(S >> 3);
+    KSteps<BITS, NT, GROUPED, S + 1>::run(wd0, wd1, xb, lane, M, acc, epi);
+  }
+};
+template <int BITS, int NT, bool GROUPED>
+struct KSteps<BITS, NT, GROUPED, 16> {
+  template <typename Epi>
+  static __device__ __forceinline__ void run(const u32 *, const u32 *, const u32x4 *, int, const Magic &, f16_t *, Epi &) {}
+};
+
+// One workgroup = 4 waves = 256 rows (a row group); wave w owns row tiles 2w, 2w+1 of it.
+template <int BITS, int NT, bool GROUPED>
+__global__ __launch_bounds__(256) void owq_tile_mma(const TileArgs a) {
+  constexpr int CH = BITS == 3 ? 3 : 4;
+  constexpr int XU = NT == 2 ? 8 : 4;           // activation units a thread stages per step
+  extern __shared__ u32x4 lds[];                // two activation tiles
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int P = gridDim.x, p = blockIdx.x;
+  const int lo = (int)((long long)p * a.steps / P), hi = (int)((long long)(p + 1) * a.steps / P);
+  if (lo >= hi) return;
+  int rg = lo / a.nbp, bp = lo - rg * a.nbp;    // the step being computed
+
+  // ---- fetch cursors: codes two steps ahead, activations one step ahead -------------
+  u32x4 cb[3][2][CH];
+  int c_st = lo, c_rg = rg, c_bp = bp;
+  auto fetch_codes = [&](int slot) {
+#pragma unroll
+    for (int rtl = 0; rtl < 2; ++rtl) {
+      const int rt = min(c_rg * kTileGroupTiles + 2 * w + rtl, a.n_rt - 1);
+      const u32x4 *src = a.codes + ((size_t)(rt * a.nbp + c_bp) * CH) * 64 + lane;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) cb[slot][rtl][c] = __builtin_nontemporal_load(src + c * 64);
+    }
+    if (c_st + 1 < hi) {                       // past the end: fetch the last step again
+      ++c_st;
+      if (++c_bp == a.nbp) { c_bp = 0; ++c_rg; }
+    }
+  };
+  u32x4 xg[XU];
+  int x_st = lo, x_bp = bp;
+  auto unit_of = [&](int j) {
+    const int i = tid + 256 * j;
+    return NT == 2 ? i : ((i >> 6) * 128 + (i & 63));
+  };
+  auto fetch_x = [&]() {
+    const u32x4 *src = a.xs + (size_t)x_bp * kUnitsPerTile;
+#pragma unroll
+    for (int j = 0; j < XU; ++j) xg[j] = src[unit_of(j)];
+    if (x_st + 1 < hi) {
+      ++x_st;
+      if (++x_bp == a.nbp) x_bp = 0;
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < XU; ++j) lds[buf * kUnitsPerTile + unit_of(j)] = xg[j];
+  };
+
+  fetch_x();
+  fetch_codes(0);
+  fetch_codes(1);
+  store_x(0);
+  __syncthreads();
+
+  Magic M;
+  M.init();
+  f16_t acc[4], tot[GROUPED ? 4 : 1];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  if (GROUPED) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tot[i][r] = 0.f;
+  }
+  int gfirst = 2 * bp;                           // first block accumulated since acc was cleared
+
+  auto flush = [&](const f16_t *v, int slot) {
+    f4_t *dst = a.slots + (size_t)slot * kSlotUnits + (w * 16) * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (NT == 1 && (i & 1)) continue;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f4_t o = {v[i][4 * q], v[i][4 * q + 1], v[i][4 * q + 2], v[i][4 * q + 3]};
+        dst[(i * 4 + q) * 64] = o;
+      }
+    }
+  };
+  auto clear = [&](f16_t *v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[i][r] = 0.f;
+  };
+  // grouped scales: tot += s * (acc - sum c*x - z * sum x) over blocks b0..b1 of group g
+  auto group_epilogue = [&](int g, int b0, int b1) {
+    if (g > a.n_groups - 1) g = a.n_groups - 1;
+    float X[2] = {0.f, 0.f}, Bc[2] = {0.f, 0.f};
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const f2_t *src = a.bsum + (size_t)(nt * 32 + (lane & 31)) * a.nblk;
+      for (int b = b0; b <= b1; ++b) {
+        const f2_t v = src[b];
+        X[nt] += v.x;
+        Bc[nt] += v.y;
+      }
+    }
+#pragma unroll
+    for (int rtl = 0; rtl < 2; ++rtl) {
+      const int rt = min(rg * kTileGroupTiles + 2 * w + rtl, a.n_rt - 1);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = rt * kTileRows + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const u32 szw = a.sz[(size_t)row * a.n_groups + g];
+        const float sc = half_lo(szw), zp = half_hi(szw);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          float v = acc[rtl * 2 + nt][r] - Bc[nt];
+          v = __builtin_fmaf(-zp, X[nt], v);
+          tot[GROUPED ? rtl * 2 + nt : 0][r] = __builtin_fmaf(sc, v, tot[GROUPED ? rtl * 2 + nt : 0][r]);
+          acc[rtl * 2 + nt][r] = 0.f;
+        }
+      }
+    }
+  };
+
+  int par = 0;
+  for (int st = lo; st < hi;) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      fetch_x();                     // activations of step st + 1
+      fetch_codes((j + 2) % 3);      // codes of step st + 2
+      if (st < hi) {
+        if (bp == 0 && a.kp > 0) {
+          // the fp16 weak columns of this row group: plain K-steps into the cleared accumulators
+          const int kunits = a.kp >> 3;
+          for (int s = 0; 2 * s < kunits; ++s) {
+            const int u = 2 * s + (lane >> 5);
+            const bool live = u < kunits;
+            const int uc = live ? u : 0;
+            u32x4 av[2], bv[2];
+#pragma unroll
+            for (int rtl = 0; rtl < 2; ++rtl) {
+              const int rt = min(rg * kTileGroupTiles + 2 * w + rtl, a.n_rt - 1);
+              av[rtl] = a.weak_w[(size_t)(rt * kTileRows + (lane & 31)) * kunits + uc];
+              if (!live) av[rtl] = (u32x4){0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+              bv[nt] = a.xw[(size_t)(nt * 32 + (lane & 31)) * kunits + uc];
+              if (!live) bv[nt] = (u32x4){0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int rtl = 0; rtl < 2; ++rtl)
+#pragma unroll
+              for (int nt = 0; nt < NT; ++nt)
+                acc[rtl * 2 + nt] = mma(__builtin_bit_cast(h8_t, av[rtl]), __builtin_bit_cast(h8_t, bv[nt]), acc[rtl * 2 + nt]);
+          }
+          flush(acc, a.weak_slot0 + rg);
+          clear(acc);
+        }
+        u32 wd0[CH * 4], wd1[CH * 4];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          wd0[4 * c] = cb[j][0][c].x; wd0[4 * c + 1] = cb[j][0][c].y; wd0[4 * c + 2] = cb[j][0][c].z; wd0[4 * c + 3] = cb[j][0][c].w;
+          wd1[4 * c] = cb[j][1][c].x; wd1[4 * c + 1] = cb[j][1][c].y; wd1[4 * c + 2] = cb[j][1][c].z; wd1[4 * c + 3] = cb[j][1][c].w;
+        }
+        auto epi = [&](int half) {
+          const int blk = 2 * bp + half;
+          if ((blk + 1) % a.bpg == 0 || blk == a.nblk - 1) {
+            group_epilogue(blk / a.bpg, gfirst, blk);
+            gfirst = blk + 1;
+          }
+        };
+        KSteps<BITS, NT, GROUPED, 0>::run(wd0, wd1, lds + par * kUnitsPerTile, lane, M, acc, epi);
+        const bool last_of_group = bp == a.nbp - 1;
+        if (last_of_group || st == hi - 1) {
+          if constexpr (GROUPED) {
+            if (gfirst <= 2 * bp + 1) group_epilogue((2 * bp + 1) / a.bpg, gfirst, 2 * bp + 1);
+            flush(tot, p + rg);
+            clear(tot);
+          } else {
+            flush(acc, p + rg);
+            clear(acc);
+          }
+        }
+        if (last_of_group) { bp = 0; ++rg; } else { ++bp; }
+        if (last_of_group) gfirst = 0;
+      }
+      store_x(par ^ 1);
+      __syncthreads();
+      par ^= 1;
+      ++st;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// finish
+// ---------------------------------------------------------------------------
+struct FinishArgs {
+  const f4_t *slots;
+  const f2_t *csum;
+  const u32 *sz;
+  _Float16 *y;           // [ntok][d_out] of this pass
+  int nbp, nchunk, d_out, d_out_pad, ntok, steps, grid, weak_slot0;
+  int scaled;            // the partial results are already scaled (grouped layers)
+  int has_weak;
+};
+
+// grid = row groups x 4: one workgroup per 64 rows (the part of a slot one wave wrote).
+__global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
+  __shared__ f2_t tsum[64];
+  __shared__ _Float16 out[64][72];     // [token][row], padded pitch
+  const int tid = threadIdx.x, lane = tid & 63, q = tid >> 6;
+  const int rg = blockIdx.x >> 2, w = blockIdx.x & 3;
+  if (!a.scaled && tid < 64) {
+    float sx = 0.f, sb = 0.f;
+    for (int c = 0; c < a.nchunk; ++c) {
+      const f2_t v = a.csum[tid * kTileChunksMax + c];
+      sx += v.x;
+      sb += v.y;
+    }
+    tsum[tid] = (f2_t){sx, sb};
+  }
+  __syncthreads();
+  // owners of the first and the last step of this row group
+  const long long s0 = (long long)rg * a.nbp, s1 = s0 + a.nbp - 1;
+  const int p_first = (int)(((s0 + 1) * a.grid - 1) / a.steps), p_last = (int)(((s1 + 1) * a.grid - 1) / a.steps);
+  const int ntiles = a.ntok > 32 ? 2 : 1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int nt = i & 1, rtl = i >> 1;
+    if (nt >= ntiles) continue;
+    const size_t unit = (size_t)((w * 4 + i) * 4 + q) * 64 + lane;
+    f4_t sum = {0.f, 0.f, 0.f, 0.f};
+    for (int p = p_first; p <= p_last; ++p) {
+      const f4_t v = a.slots[(size_t)(p + rg) * kSlotUnits + unit];
+      sum += v;
+    }
+    const int n = nt * 32 + (lane & 31);
+    const int r0 = rtl * 32 + 8 * q + 4 * (lane >> 5);      // row within the wave's 64
+    if (!a.scaled) {
+      int row = rg * 256 + w * 64 + r0;
+      if (row > a.d_out_pad - 4) row = a.d_out_pad - 4;
+      const u32x4 szw = *reinterpret_cast<const u32x4 *>(a.sz + row);
+      const f2_t t = tsum[n];
+      const u32 s4[4] = {szw.x, szw.y, szw.z, szw.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float v = sum[e] - t.y;
+        v = __builtin_fmaf(-half_hi(s4[e]), t.x, v);
+        sum[e] = v * half_lo(s4[e]);
+      }
+    }
+    if (a.has_weak) sum += a.slots[(size_t)(a.weak_slot0 + rg) * kSlotUnits + unit];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[n][r0 + e] = (_Float16)sum[e];
+  }
+  __syncthreads();
+  const int row_base = rg * 256 + w * 64;
+  for (int e = tid; e < a.ntok * 64; e += 256) {
+    const int n = e >> 6, r = e & 63;
+    if (row_base + r < a.d_out) a.y[(size_t)n * a.d_out + row_base + r] = out[n][r];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+typedef void (*mma_fn)(const TileArgs);
+
+static mma_fn pick_mma(int bits, int nt, bool grouped) {
+  if (bits == 3) {
+    if (nt == 2) return grouped ? owq_tile_mma<3, 2, true> : owq_tile_mma<3, 2, false>;
+    return grouped ? owq_tile_mma<3, 1, true> : owq_tile_mma<3, 1, false>;
+  }
+  if (nt == 2) return grouped ? owq_tile_mma<4, 2, true> : owq_tile_mma<4, 2, false>;
+  return grouped ? owq_tile_mma<4, 1, true> : owq_tile_mma<4, 1, false>;
+}
+
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void *x, void *y,
+                int32_t batch, void *stream) {
+  const TileScratch ts = tile_scratch(g);
+  uint8_t *base = static_cast<uint8_t *>(blob);
+  uint8_t *scr = base + g.off_scratch;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool grouped = g.n_groups > 1;
+  if (grid < 1 || grid > ts.grid_max) return (int)hipErrorInvalidValue;
+
+  StageArgs sa;
+  sa.wmask = base + g.off_wmask;
+  sa.weak_idx = reinterpret_cast<const int *>(base + g.off_weak_idx);
+  sa.xs = reinterpret_cast<u32x4 *>(scr + ts.off_xs);
+  sa.bsum = reinterpret_cast<f2_t *>(scr + ts.off_bsum);
+  sa.csum = reinterpret_cast<f2_t *>(scr + ts.off_csum);
+  sa.xw = reinterpret_cast<_Float16 *>(scr + ts.off_xw);
+  sa.d_in = g.d_in; sa.nbp = g.nbp; sa.nblk = g.nblk; sa.kp = g.kp;
+  sa.nchunk = g.nbp < kTileChunksMax ? g.nbp : kTileChunksMax;
+
+  TileArgs ta;
+  ta.codes = reinterpret_cast<const u32x4 *>(base + g.off_codes);
+  ta.sz = reinterpret_cast<const u32 *>(base + g.off_sz);
+  ta.weak_w = reinterpret_cast<const u32x4 *>(base + g.off_weak_w);
+  ta.xs = sa.xs;
+  ta.bsum = sa.bsum;
+  ta.xw = reinterpret_cast<const u32x4 *>(sa.xw);
+  ta.slots = reinterpret_cast<f4_t *>(scr + ts.off_slots);
+  ta.nbp = g.nbp; ta.n_rt = g.n_rt; ta.n_groups = g.n_groups; ta.nblk = g.nblk; ta.kp = g.kp;
+  ta.bpg = g.group_size ? g.group_size / kBlockCols : g.nblk;
+  ta.steps = ts.n_rg * g.nbp;
+  ta.weak_slot0 = ts.grid_max + ts.n_rg;
+
+  FinishArgs fa;
+  fa.slots = ta.slots;
+  fa.csum = sa.csum;
+  fa.sz = ta.sz;
+  fa.nbp = g.nbp; fa.nchunk = sa.nchunk; fa.d_out = g.d_out; fa.d_out_pad = g.d_out_pad;
+  fa.steps = ta.steps; fa.grid = grid; fa.weak_slot0 = ta.weak_slot0;
+  fa.scaled = grouped ? 1 : 0;
+  fa.has_weak = g.kp > 0 ? 1 : 0;
+
+  const _Float16 *xp = static_cast<const _Float16 *>(x);
+  _Float16 *yp = static_cast<_Float16 *>(y);
+  for (int32_t t0 = 0; t0 < batch; t0 += kScratchBatch) {
+    const int ntok = batch - t0 < kScratchBatch ? batch - t0 : kScratchBatch;
+    const int nt = ntok > 32 ? 2 : 1;
+    sa.x = xp + (size_t)t0 * g.d_in;
+    sa.ntok = ntok;
+    if (g.bits == 3)
+      hipLaunchKernelGGL(owq_tile_stage<3>, dim3((unsigned)sa.nchunk, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
+    else
+      hipLaunchKernelGGL(owq_tile_stage<4>, dim3((unsigned)sa.nchunk, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
+    hipLaunchKernelGGL(pick_mma(g.bits, nt, grouped), dim3((unsigned)grid, 1, 1), dim3(256, 1, 1),
+                       2 * kUnitsPerTile * 16, st, ta);
+    fa.y = yp + (size_t)t0 * g.d_out;
+    fa.ntok = ntok;
+    hipLaunchKernelGGL(owq_tile_finish, dim3((unsigned)(ts.n_rg * 4), 1, 1), dim3(256, 1, 1), 0, st, fa);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return (int)hipSuccess;
+}
+
+}  // namespace owq
