@@ -23,14 +23,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
 
 WORKLOADS = {
-    # name: (config index in the benchmark's list, layer indices, description)
-    "opt6.7b-ffn": (2, [0, 1], "configs[2]: OPT-6.7B-like FFN pair, fc1 4096->16384 (k=32) + fc2 16384->4096 (k=128), 3-bit, group 128, batch 1"),
-    "opt6.7b-attn": (1, [0], "configs[1]: OPT-6.7B-like attention projection 4096->4096, 3-bit per-channel, k=32, batch 1"),
-    "target": (5, [0], "bandwidth-target layer 16384->4096, 3-bit per-channel, k=128, batch 1"),
-    "llama13b": (3, [0, 1, 2], "configs[3]: LLaMA-13B-like q/k/v/o, gate/up, down, 4-bit group 128, k=1%"),
-    "tiny": (0, [0], "configs[0]: 1024->1024, 4-bit per-channel, k=8, batch 1"),
+    # name: (config index in the benchmark's list, layer indices, description, packed layout, default batch)
+    "opt6.7b-ffn": (2, [0, 1], "configs[2]: OPT-6.7B-like FFN pair, fc1 4096->16384 (k=32) + fc2 16384->4096 (k=128), 3-bit, group 128", 0, 1),
+    "opt6.7b-attn": (1, [0], "configs[1]: OPT-6.7B-like attention projection 4096->4096, 3-bit per-channel, k=32", 0, 1),
+    "target": (5, [0], "bandwidth-target layer 16384->4096, 3-bit per-channel, k=128", 0, 1),
+    "llama13b": (3, [0, 1, 2], "configs[3]: LLaMA-13B-like q/k/v/o, gate/up, down, 4-bit group 128, k=1%", 0, 1),
+    "tiny": (0, [0], "configs[0]: 1024->1024, 4-bit per-channel, k=8", 0, 1),
+    "opt66b-ffn": (4, [0, 1], "configs[4]: OPT-66B-like FFN pair, fc1 9216->36864 (k=64) + fc2 36864->9216 (k=256), 3-bit per-channel, tile layout (matrix cores)", 1, 64),
 }
 
 
@@ -47,7 +49,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="opt6.7b-ffn", choices=sorted(WORKLOADS))
-    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--batch", type=int, default=0, help="tokens per call (default: the workload's own)")
+    ap.add_argument("--layout", type=int, default=-1, help="0 = single-token layout, 1 = tile layout (default: the workload's own)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K timed steps are one HIP graph launch; eager: K*layers launches from Python")
     ap.add_argument("--footprint-gb", type=float, default=1.5, help="total bytes of packed copies to rotate over")
@@ -69,9 +72,12 @@ def main() -> int:
     B.lib()                                       # no library, no benchmark
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    cfg, layer_ids, desc = WORKLOADS[args.workload]
+    cfg, layer_ids, desc, layout, batch = WORKLOADS[args.workload]
     specs = [CONFIGS[cfg][i] for i in layer_ids]
-    batch = args.batch
+    if args.batch:
+        batch = args.batch
+    if args.layout >= 0:
+        layout = args.layout
 
     layers = [make_layer(s) for s in specs]
     xs_host = [make_x(L, batch) for L in layers]
@@ -79,12 +85,13 @@ def main() -> int:
     step_bytes = sum(bytes_per_layer)
 
     # packed copies to rotate over
-    first = [B.OwqLinear(L) for L in layers]
+    first = [B.OwqLinear(L, layout=layout) for L in layers]
     packed_total = sum(int(f.buf.numel()) for f in first)
     copies = max(1, int(-(-args.footprint_gb * 1e9 // packed_total)))
-    sets = [first] + [[B.OwqLinear(L, packed=f.buf) for L, f in zip(layers, first)] for _ in range(copies - 1)]
+    sets = [first] + [[B.OwqLinear(L, packed=f.buf, layout=layout) for L, f in zip(layers, first)]
+                      for _ in range(copies - 1)]
     if args.launch:
-        rtw, rsplit, waves, depth = (int(v) for v in args.launch.split(","))
+        rtw, rsplit, waves, depth = (int(v) for v in (args.launch.split(",") + ["0", "0", "0"])[:4])
         for st in sets:
             for lin in st:
                 B.owq_set_launch(lin.handle, rtw, rsplit, waves, depth)
@@ -142,6 +149,23 @@ def main() -> int:
         except Exception:
             traffic = None
     info = first[0].info()
+    flops_per_step = sum(2 * batch * sp.d_out * (sp.d_in + sp.k) for sp in specs)
+    if layout == 1:
+        # three kernels per call; the matrix kernel dominates.  The figure charges the whole call to it.
+        tflops = flops_per_step / len(specs) / avg_launch_s / 1e12
+        roofline = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": traffic,
+                    "kernel": f"owq_tile_mma<{specs[0].bits},{2 if batch > 32 else 1}> (+ stage, finish)",
+                    "avg_launch_us": round(avg_launch_s * 1e6, 3),
+                    "flops_per_launch": flops_per_step // len(specs),
+                    "hbm_gbs": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "workgroups": info.workgroups}
+    else:
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                    "kernel": f"owq_gemv_kernel<{specs[0].bits},{info.prefetch_depth}>",
+                    "avg_launch_us": round(avg_launch_s * 1e6, 3),
+                    "bytes_per_launch": step_bytes // len(specs)}
     result = {
         "metric": "effective HBM GB/s (% of peak) + us/call, 3-bit OWQ linear, batch 1",
         "value": round(value, 1),
@@ -160,11 +184,7 @@ def main() -> int:
                    "bytes_per_step": step_bytes},
         "pct_of_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "us_per_call": round(wall_s / launches * 1e6, 3),
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": f"owq_gemv_kernel<{specs[0].bits},{info.prefetch_depth}>",
-                     "avg_launch_us": round(avg_launch_s * 1e6, 3),
-                     "bytes_per_launch": step_bytes // len(specs)},
+        "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
@@ -174,13 +194,25 @@ def main() -> int:
             threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             threads = os.cpu_count() or 1
-        c0 = time.perf_counter()
-        for L, x in zip(layers, xs_host):
-            owq_ref.owq_linear_layer(L, x)
+        # a bounded sample of the same step: the first `rows` output rows of every layer (all of
+        # them when the step is small), repeated until about ten seconds have gone by
+        work = sum(sp.d_out * sp.d_in * batch for sp in specs)
+        frac = min(1.0, 2.0e9 / work)
+        reps, c0 = 0, time.perf_counter()
+        while True:
+            for L, x in zip(layers, xs_host):
+                rows = max(1, int(L.d_out * frac))
+                owq_ref.owq_linear_ref(L.codes[:rows], L.scale[:rows], L.zero[:rows], L.group_size,
+                                       L.weak_idx, L.weak_w[:rows], x)
+            reps += 1
+            if time.perf_counter() - c0 >= 10.0:
+                break
         c1 = time.perf_counter()
-        result["cpu_baseline"] = {"value": round(step_bytes / (c1 - c0) / 1e9, 4), "unit": "GB/s",
+        cpu_steps = reps * frac
+        result["cpu_baseline"] = {"value": round(step_bytes * cpu_steps / (c1 - c0) / 1e9, 4), "unit": "GB/s",
                                   "cores": int(threads), "kind": "oracle",
-                                  "sample": f"1 step ({len(specs)} full layers, batch {batch}) in {c1 - c0:.2f} s"}
+                                  "sample": f"{reps} x the first {100 * frac:.1f} % of the output rows of each of the "
+                                            f"{len(specs)} layers, batch {batch}, in {c1 - c0:.2f} s"}
     print(json.dumps(result), flush=True)
     for st in sets:
         for lin in st:
