@@ -21,17 +21,16 @@ constexpr int kScratchBatch = 64;    // tokens per pass of the tile path
 constexpr int kTileGroupTiles = 8;   // row tiles per row group (one workgroup: 4 waves x 2 tiles)
 constexpr int kTileGridMax = 512;    // most workgroups of the tile kernel
 constexpr int kTileSlotBytes = 65536;  // one partial result: 256 rows x 64 tokens, fp32
-constexpr int kTileChunksMax = 32;   // most column chunks of the staging kernel
 
 // Map of the scratch area of a tile-layout blob (byte offsets from off_scratch).
 struct TileScratch {
   int32_t n_rg;          // row groups of 256 rows
   int32_t grid_max;      // most workgroups the partial slots allow: min(kTileGridMax, n_rg * nbp)
   uint64_t off_xs;       // staged activations: [nbp][16 k-steps][2 token tiles][64 lanes][8 fp16]
-  uint64_t off_bsum;     // [64 tokens][nblk] (sum x, sum c*x) as two floats
-  uint64_t off_csum;     // [64 tokens][kTileChunksMax] the same per column chunk
+  uint64_t off_bsum;     // [nblk][64 tokens] (sum x, sum c*x) as two floats
+  uint64_t off_tsum;     // [64 tokens] the same summed over all blocks (16 KiB reserved)
   uint64_t off_xw;       // [64 tokens][kp] fp16: activations at the weak columns
-  uint64_t off_slots;    // partial results: grid_max + n_rg dense slots, then n_rg weak slots
+  uint64_t off_slots;    // partial results: grid_max + n_rg slots in use (room for n_rg more)
   uint64_t total;
 };
 TileScratch tile_scratch(const owq_layer_info_t &g);

@@ -23,8 +23,8 @@ TileScratch tile_scratch(const owq_layer_info_t &g) {
   t.grid_max = steps < kTileGridMax ? (int32_t)steps : kTileGridMax;
   t.off_xs = 0;
   t.off_bsum = t.off_xs + (uint64_t)kScratchBatch * g.nbp * 256 * 2;
-  t.off_csum = t.off_bsum + (uint64_t)g.nblk * kScratchBatch * 8;
-  t.off_xw = t.off_csum + (uint64_t)kScratchBatch * kTileChunksMax * 8;
+  t.off_tsum = t.off_bsum + (uint64_t)g.nblk * kScratchBatch * 8;
+  t.off_xw = t.off_tsum + 16384;
   t.off_slots = t.off_xw + (uint64_t)kScratchBatch * g.kp * 2;
   t.total = t.off_slots + (uint64_t)(t.grid_max + 2 * t.n_rg) * kTileSlotBytes;
   return t;

@@ -11,16 +11,18 @@
 //   stage   copies x into the order the matrix instruction reads it, clears the weak
 //           columns (by select), gathers x at the weak indices and sums, per token and
 //           block, x and c*x (c = the constant each code is OR-ed into, see below);
+//           one workgroup per 256 columns and 32 tokens;
 //   mma     every wave owns 64 rows x 64 tokens of fp32 accumulators and walks along the
 //           columns: codes go from registers straight into the A operand (a pair of codes
 //           is masked out of a dword and OR-ed into the mantissas of 2^(10-o), giving
 //           2^(10-o)+q exactly), tokens come from LDS as the B operand.  The flattened
 //           (row group, column step) sequence is cut into equal ranges, one per workgroup,
 //           so that all compute units stay busy whatever the shape; a workgroup writes one
-//           partial result per row group it touches.  The fp16 weak columns are further
-//           K-steps whose result goes to a slot of its own (it must not be scaled);
+//           partial result per row group it touches.  While their first loads are in
+//           flight the first 64 workgroups add up the block sums of one token each;
 //   finish  adds the partial results of a row group in a fixed order, removes the constant
-//           part and the zero point, scales, adds the weak product, rounds to fp16.
+//           part and the zero point, scales, adds the product of the fp16 weak columns
+//           (a few more K-steps on the matrix cores), rounds to fp16.
 // No atomics: results are reproducible.
 #include <hip/hip_runtime.h>
 
@@ -53,22 +55,19 @@ struct StageArgs {
   const unsigned char *wmask;  // bit e of byte i: column 8i+e is weak
   const int *weak_idx;         // [kp], padding -1
   u32x4 *xs;                   // [nbp][16][2][64] units
-  f2_t *bsum;                  // [64][nblk]
-  f2_t *csum;                  // [64][kTileChunksMax]
+  f2_t *bsum;                  // [nblk][64]
   _Float16 *xw;                // [64][kp]
-  int d_in, ntok, nbp, nblk, kp, nchunk;
+  int d_in, ntok, nblk, kp;
 };
 
-// grid (column chunk, token tile of 32); thread = (token, one of 8 octets per trip).
+// grid (block pair, token tile of 32); thread = (token, octets oo, oo+8, oo+16, oo+24 of the pair).
 template <int BITS>
 __global__ __launch_bounds__(256) void owq_tile_stage(const StageArgs a) {
   __shared__ f2_t red[8][2][32];
-  __shared__ f2_t ctot[2][32];
   const int tid = threadIdx.x, nl = tid & 31, oo = tid >> 5;
-  const int c = blockIdx.x, nt = blockIdx.y;
+  const int bp = blockIdx.x, nt = blockIdx.y;
   const int n = nt * 32 + nl;
   const bool valid = n < a.ntok;
-  const int bp0 = (int)((long long)c * a.nbp / a.nchunk), bp1 = (int)((long long)(c + 1) * a.nbp / a.nchunk);
   const _Float16 *xr = a.x + (size_t)(valid ? n : 0) * a.d_in;
   const bool vec = ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0) && ((a.d_in & 7) == 0);
   // octet o = 8*trip + oo of the pair: k-step (o >> 1) & 7, whose place in its quad is (oo >> 1) & 3
@@ -81,72 +80,66 @@ __global__ __launch_bounds__(256) void owq_tile_stage(const StageArgs a) {
       if (((oo >> 1) & 3) == q) v = (float)(1 << (10 - pair_offset(BITS, q, i)));
     cst[i] = v;
   }
-  float cx = 0.f, cb = 0.f;
-  for (int bp = bp0; bp < bp1; ++bp) {
-    float X[2] = {0.f, 0.f}, Bc[2] = {0.f, 0.f};
+  u32 w[4][4];
+  u32 m[4];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int o = it * 8 + oo;
-      const int j0 = bp * 256 + o * 8;
-      u32 w[4] = {0u, 0u, 0u, 0u};
-      if (valid && j0 < a.d_in) {
-        if (vec) {
-          const u32x4 v = *reinterpret_cast<const u32x4 *>(xr + j0);
-          w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-        } else {
+  for (int it = 0; it < 4; ++it) {
+    const int o = it * 8 + oo;
+    const int j0 = bp * 256 + o * 8;
+    w[it][0] = w[it][1] = w[it][2] = w[it][3] = 0u;
+    if (valid && j0 < a.d_in) {
+      if (vec) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(xr + j0);
+        w[it][0] = v.x; w[it][1] = v.y; w[it][2] = v.z; w[it][3] = v.w;
+      } else {
 #pragma unroll
-          for (int t = 0; t < 8; ++t) {
-            const int j = j0 + t;
-            const u32 h = j < a.d_in ? (u32)__builtin_bit_cast(unsigned short, xr[j]) : 0u;
-            w[t >> 1] |= h << (16 * (t & 1));
-          }
+        for (int t = 0; t < 8; ++t) {
+          const int j = j0 + t;
+          const u32 h = j < a.d_in ? (u32)__builtin_bit_cast(unsigned short, xr[j]) : 0u;
+          w[it][t >> 1] |= h << (16 * (t & 1));
         }
       }
-      const u32 m = a.wmask[bp * 32 + o];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {        // weak columns contribute nothing to the dense term
-        if (m & (1u << (2 * i))) w[i] &= 0xffff0000u;
-        if (m & (2u << (2 * i))) w[i] &= 0x0000ffffu;
-      }
-      if (valid) {
-        const u32x4 v = {w[0], w[1], w[2], w[3]};
-        a.xs[((size_t)(bp * 16 + (o >> 1)) * 2 + nt) * 64 + (o & 1) * 32 + nl] = v;
-      }
-      float sx = 0.f, sb = 0.f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float pr = dot2(w[i], kOnes, 0.f);
-        sx += pr;
-        sb = __builtin_fmaf(pr, cst[i], sb);
-      }
-      X[it >> 1] += sx;
-      Bc[it >> 1] += sb;
     }
-    red[oo][0][nl] = (f2_t){X[0], Bc[0]};
-    red[oo][1][nl] = (f2_t){X[1], Bc[1]};
-    __syncthreads();
-    if (tid < 64) {
-      const int b = tid >> 5;
-      float sx = 0.f, sb = 0.f;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const f2_t r = red[q][b][nl];
-        sx += r.x;
-        sb += r.y;
-      }
-      if (valid) a.bsum[(size_t)n * a.nblk + 2 * bp + b] = (f2_t){sx, sb};
-      cx += sx;
-      cb += sb;
-    }
-    __syncthreads();
+    m[it] = a.wmask[bp * 32 + o];
   }
-  if (tid < 64) ctot[tid >> 5][nl] = (f2_t){cx, cb};
+  float X[2] = {0.f, 0.f}, Bc[2] = {0.f, 0.f};
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int o = it * 8 + oo;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {        // weak columns contribute nothing to the dense term
+      if (m[it] & (1u << (2 * i))) w[it][i] &= 0xffff0000u;
+      if (m[it] & (2u << (2 * i))) w[it][i] &= 0x0000ffffu;
+    }
+    if (valid) {
+      const u32x4 v = {w[it][0], w[it][1], w[it][2], w[it][3]};
+      a.xs[((size_t)(bp * 16 + (o >> 1)) * 2 + nt) * 64 + (o & 1) * 32 + nl] = v;
+    }
+    float sx = 0.f, sb = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float pr = dot2(w[it][i], kOnes, 0.f);
+      sx += pr;
+      sb = __builtin_fmaf(pr, cst[i], sb);
+    }
+    X[it >> 1] += sx;
+    Bc[it >> 1] += sb;
+  }
+  red[oo][0][nl] = (f2_t){X[0], Bc[0]};
+  red[oo][1][nl] = (f2_t){X[1], Bc[1]};
   __syncthreads();
-  if (tid < 32 && valid) {
-    const f2_t u = ctot[0][nl], v = ctot[1][nl];
-    a.csum[n * kTileChunksMax + c] = (f2_t){u.x + v.x, u.y + v.y};
+  if (tid < 64 && valid) {
+    const int b = tid >> 5;
+    float sx = 0.f, sb = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const f2_t r = red[q][b][nl];
+      sx += r.x;
+      sb += r.y;
+    }
+    a.bsum[(size_t)(2 * bp + b) * 64 + n] = (f2_t){sx, sb};
   }
-  if (c == 0) {
+  if (bp == 0) {
     for (int e = tid; e < 32 * a.kp; e += 256) {
       const int ln = e / a.kp, t = e - ln * a.kp, nn = nt * 32 + ln;
       if (nn < a.ntok) {
@@ -163,14 +156,12 @@ __global__ __launch_bounds__(256) void owq_tile_stage(const StageArgs a) {
 struct TileArgs {
   const u32x4 *codes;
   const u32 *sz;
-  const u32x4 *weak_w;   // [d_out_pad][kp/8] units
   const u32x4 *xs;
   const f2_t *bsum;
-  const u32x4 *xw;       // [64][kp/8] units
+  f2_t *tsum;            // [64]: per token, sum over all blocks of (x, c*x)
   f4_t *slots;
-  int nbp, n_rt, n_groups, bpg, nblk, kp;
+  int nbp, n_rt, n_groups, bpg, nblk;
   int steps;             // row groups x column steps
-  int weak_slot0;        // first weak slot
 };
 
 // A operand of k-step S (16 columns) from the lane's dwords: four packed pairs 2^(10-o)+q.
@@ -236,8 +227,10 @@ struct KSteps<BITS, NT, GROUPED, 16> {
 };
 
 // One workgroup = 4 waves = 256 rows (a row group); wave w owns row tiles 2w, 2w+1 of it.
+// Two workgroups share a compute unit (two waves per SIMD, at most 256 registers each) so that
+// one computes while the other waits at its barrier or for its loads.
 template <int BITS, int NT, bool GROUPED>
-__global__ __launch_bounds__(256) void owq_tile_mma(const TileArgs a) {
+__global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileArgs a) {
   constexpr int CH = BITS == 3 ? 3 : 4;
   constexpr int XU = NT == 2 ? 8 : 4;           // activation units a thread stages per step
   extern __shared__ u32x4 lds[];                // two activation tiles
@@ -286,6 +279,31 @@ __global__ __launch_bounds__(256) void owq_tile_mma(const TileArgs a) {
   fetch_x();
   fetch_codes(0);
   fetch_codes(1);
+  if (!GROUPED) {
+    // While the first loads are in flight: the sums over all blocks of token n, for the
+    // finish kernel (layers with one scale per row only).  Fixed order of additions.
+    __shared__ f2_t tred[4];
+    for (int n = p; n < kScratchBatch; n += P) {
+      float sx = 0.f, sb = 0.f;
+      for (int b = tid; b < a.nblk; b += 256) {
+        const f2_t v = a.bsum[(size_t)b * 64 + n];
+        sx += v.x;
+        sb += v.y;
+      }
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) {
+        sx += __shfl_xor(sx, d);
+        sb += __shfl_xor(sb, d);
+      }
+      if (lane == 0) tred[w] = (f2_t){sx, sb};
+      __syncthreads();
+      if (tid == 0) {
+        const f2_t u0 = tred[0], u1 = tred[1], u2 = tred[2], u3 = tred[3];
+        a.tsum[n] = (f2_t){(u0.x + u1.x) + (u2.x + u3.x), (u0.y + u1.y) + (u2.y + u3.y)};
+      }
+      __syncthreads();
+    }
+  }
   store_x(0);
   __syncthreads();
 
@@ -328,9 +346,9 @@ __global__ __launch_bounds__(256) void owq_tile_mma(const TileArgs a) {
     float X[2] = {0.f, 0.f}, Bc[2] = {0.f, 0.f};
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const f2_t *src = a.bsum + (size_t)(nt * 32 + (lane & 31)) * a.nblk;
+      const f2_t *src = a.bsum + nt * 32 + (lane & 31);
       for (int b = b0; b <= b1; ++b) {
-        const f2_t v = src[b];
+        const f2_t v = src[(size_t)b * 64];
         X[nt] += v.x;
         Bc[nt] += v.y;
       }
@@ -361,34 +379,6 @@ __global__ __launch_bounds__(256) void owq_tile_mma(const TileArgs a) {
       fetch_x();                     // activations of step st + 1
       fetch_codes((j + 2) % 3);      // codes of step st + 2
       if (st < hi) {
-        if (bp == 0 && a.kp > 0) {
-          // the fp16 weak columns of this row group: plain K-steps into the cleared accumulators
-          const int kunits = a.kp >> 3;
-          for (int s = 0; 2 * s < kunits; ++s) {
-            const int u = 2 * s + (lane >> 5);
-            const bool live = u < kunits;
-            const int uc = live ? u : 0;
-            u32x4 av[2], bv[2];
-#pragma unroll
-            for (int rtl = 0; rtl < 2; ++rtl) {
-              const int rt = min(rg * kTileGroupTiles + 2 * w + rtl, a.n_rt - 1);
-              av[rtl] = a.weak_w[(size_t)(rt * kTileRows + (lane & 31)) * kunits + uc];
-              if (!live) av[rtl] = (u32x4){0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-              bv[nt] = a.xw[(size_t)(nt * 32 + (lane & 31)) * kunits + uc];
-              if (!live) bv[nt] = (u32x4){0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-            for (int rtl = 0; rtl < 2; ++rtl)
-#pragma unroll
-              for (int nt = 0; nt < NT; ++nt)
-                acc[rtl * 2 + nt] = mma(__builtin_bit_cast(h8_t, av[rtl]), __builtin_bit_cast(h8_t, bv[nt]), acc[rtl * 2 + nt]);
-          }
-          flush(acc, a.weak_slot0 + rg);
-          clear(acc);
-        }
         u32 wd0[CH * 4], wd1[CH * 4];
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
@@ -430,62 +420,87 @@ __global__ __launch_bounds__(256) void owq_tile_mma(const TileArgs a) {
 // ---------------------------------------------------------------------------
 struct FinishArgs {
   const f4_t *slots;
-  const f2_t *csum;
+  const f2_t *tsum;      // [64]
   const u32 *sz;
+  const u32x4 *weak_w;   // [d_out_pad][kp/8] units
+  const u32x4 *xw;       // [64][kp/8] units
   _Float16 *y;           // [ntok][d_out] of this pass
-  int nbp, nchunk, d_out, d_out_pad, ntok, steps, grid, weak_slot0;
+  int nbp, d_out, d_out_pad, ntok, steps, grid, kp;
   int scaled;            // the partial results are already scaled (grouped layers)
-  int has_weak;
 };
 
-// grid = row groups x 4: one workgroup per 64 rows (the part of a slot one wave wrote).
+// grid = row groups x 4: one workgroup per 64 rows (the part of a slot one wave of the
+// main kernel wrote); wave i takes accumulator tile i = (row tile i >> 1, token tile i & 1).
 __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
-  __shared__ f2_t tsum[64];
   __shared__ _Float16 out[64][72];     // [token][row], padded pitch
-  const int tid = threadIdx.x, lane = tid & 63, q = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, i = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rg = blockIdx.x >> 2, w = blockIdx.x & 3;
-  if (!a.scaled && tid < 64) {
-    float sx = 0.f, sb = 0.f;
-    for (int c = 0; c < a.nchunk; ++c) {
-      const f2_t v = a.csum[tid * kTileChunksMax + c];
-      sx += v.x;
-      sb += v.y;
-    }
-    tsum[tid] = (f2_t){sx, sb};
-  }
-  __syncthreads();
-  // owners of the first and the last step of this row group
-  const long long s0 = (long long)rg * a.nbp, s1 = s0 + a.nbp - 1;
-  const int p_first = (int)(((s0 + 1) * a.grid - 1) / a.steps), p_last = (int)(((s1 + 1) * a.grid - 1) / a.steps);
+  const int nt = i & 1, rtl = i >> 1;
   const int ntiles = a.ntok > 32 ? 2 : 1;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int nt = i & 1, rtl = i >> 1;
-    if (nt >= ntiles) continue;
-    const size_t unit = (size_t)((w * 4 + i) * 4 + q) * 64 + lane;
-    f4_t sum = {0.f, 0.f, 0.f, 0.f};
-    for (int p = p_first; p <= p_last; ++p) {
-      const f4_t v = a.slots[(size_t)(p + rg) * kSlotUnits + unit];
-      sum += v;
-    }
+  if (nt < ntiles) {
     const int n = nt * 32 + (lane & 31);
-    const int r0 = rtl * 32 + 8 * q + 4 * (lane >> 5);      // row within the wave's 64
-    if (!a.scaled) {
-      int row = rg * 256 + w * 64 + r0;
-      if (row > a.d_out_pad - 4) row = a.d_out_pad - 4;
-      const u32x4 szw = *reinterpret_cast<const u32x4 *>(a.sz + row);
-      const f2_t t = tsum[n];
-      const u32 s4[4] = {szw.x, szw.y, szw.z, szw.w};
+    // product of the fp16 weak columns with the activations gathered at their indices
+    f16_t wk;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float v = sum[e] - t.y;
-        v = __builtin_fmaf(-half_hi(s4[e]), t.x, v);
-        sum[e] = v * half_lo(s4[e]);
+    for (int r = 0; r < 16; ++r) wk[r] = 0.f;
+    const int kunits = a.kp >> 3;
+    if (kunits > 0) {
+      int row = rg * 256 + w * 64 + rtl * 32 + (lane & 31);
+      if (row > a.d_out_pad - 1) row = a.d_out_pad - 1;
+      const u32x4 *wsrc = a.weak_w + (size_t)row * kunits, *xsrc = a.xw + (size_t)n * kunits;
+      const int kg = lane >> 5;
+      for (int s0 = 0; 2 * s0 < kunits; s0 += 4) {
+        u32x4 av[4], bv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {      // four K-steps of loads in flight
+          const int u = 2 * (s0 + j) + kg;
+          const bool live = u < kunits;
+          const int uc = live ? u : 0;
+          av[j] = wsrc[uc];
+          bv[j] = xsrc[uc];
+          if (!live) av[j] = (u32x4){0u, 0u, 0u, 0u};
+          if (!live) bv[j] = (u32x4){0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wk = mma(__builtin_bit_cast(h8_t, av[j]), __builtin_bit_cast(h8_t, bv[j]), wk);
       }
     }
-    if (a.has_weak) sum += a.slots[(size_t)(a.weak_slot0 + rg) * kSlotUnits + unit];
+    // owners of the first and the last step of this row group
+    const long long st0 = (long long)rg * a.nbp, st1 = st0 + a.nbp - 1;
+    const int p_first = (int)(((st0 + 1) * a.grid - 1) / a.steps), p_last = (int)(((st1 + 1) * a.grid - 1) / a.steps);
+    f2_t t = {0.f, 0.f};
+    if (!a.scaled) t = a.tsum[n];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) out[n][r0 + e] = (_Float16)sum[e];
+    for (int q = 0; q < 4; ++q) {
+      const size_t unit = (size_t)((w * 4 + i) * 4 + q) * 64 + lane;
+      f4_t sum = {0.f, 0.f, 0.f, 0.f};
+      for (int p = p_first; p <= p_last; p += 4) {   // fixed order of additions, four loads in flight
+        f4_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int pc = p + j <= p_last ? p + j : p_last;
+          v[j] = a.slots[(size_t)(pc + rg) * kSlotUnits + unit];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (p + j <= p_last) sum += v[j];
+      }
+      const int r0 = rtl * 32 + 8 * q + 4 * (lane >> 5);      // row within the workgroup's 64
+      if (!a.scaled) {
+        int row = rg * 256 + w * 64 + r0;
+        if (row > a.d_out_pad - 4) row = a.d_out_pad - 4;
+        const u32x4 szw = *reinterpret_cast<const u32x4 *>(a.sz + row);
+        const u32 s4[4] = {szw.x, szw.y, szw.z, szw.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float v = sum[e] - t.y;
+          v = __builtin_fmaf(-half_hi(s4[e]), t.x, v);
+          sum[e] = v * half_lo(s4[e]);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[n][r0 + e] = (_Float16)(sum[e] + wk[4 * q + e]);
+    }
   }
   __syncthreads();
   const int row_base = rg * 256 + w * 64;
@@ -523,32 +538,29 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void 
   sa.weak_idx = reinterpret_cast<const int *>(base + g.off_weak_idx);
   sa.xs = reinterpret_cast<u32x4 *>(scr + ts.off_xs);
   sa.bsum = reinterpret_cast<f2_t *>(scr + ts.off_bsum);
-  sa.csum = reinterpret_cast<f2_t *>(scr + ts.off_csum);
   sa.xw = reinterpret_cast<_Float16 *>(scr + ts.off_xw);
-  sa.d_in = g.d_in; sa.nbp = g.nbp; sa.nblk = g.nblk; sa.kp = g.kp;
-  sa.nchunk = g.nbp < kTileChunksMax ? g.nbp : kTileChunksMax;
+  sa.d_in = g.d_in; sa.nblk = g.nblk; sa.kp = g.kp;
 
   TileArgs ta;
   ta.codes = reinterpret_cast<const u32x4 *>(base + g.off_codes);
   ta.sz = reinterpret_cast<const u32 *>(base + g.off_sz);
-  ta.weak_w = reinterpret_cast<const u32x4 *>(base + g.off_weak_w);
   ta.xs = sa.xs;
   ta.bsum = sa.bsum;
-  ta.xw = reinterpret_cast<const u32x4 *>(sa.xw);
+  ta.tsum = reinterpret_cast<f2_t *>(scr + ts.off_tsum);
   ta.slots = reinterpret_cast<f4_t *>(scr + ts.off_slots);
-  ta.nbp = g.nbp; ta.n_rt = g.n_rt; ta.n_groups = g.n_groups; ta.nblk = g.nblk; ta.kp = g.kp;
+  ta.nbp = g.nbp; ta.n_rt = g.n_rt; ta.n_groups = g.n_groups; ta.nblk = g.nblk;
   ta.bpg = g.group_size ? g.group_size / kBlockCols : g.nblk;
   ta.steps = ts.n_rg * g.nbp;
-  ta.weak_slot0 = ts.grid_max + ts.n_rg;
 
   FinishArgs fa;
   fa.slots = ta.slots;
-  fa.csum = sa.csum;
+  fa.tsum = ta.tsum;
   fa.sz = ta.sz;
-  fa.nbp = g.nbp; fa.nchunk = sa.nchunk; fa.d_out = g.d_out; fa.d_out_pad = g.d_out_pad;
-  fa.steps = ta.steps; fa.grid = grid; fa.weak_slot0 = ta.weak_slot0;
+  fa.weak_w = reinterpret_cast<const u32x4 *>(base + g.off_weak_w);
+  fa.xw = reinterpret_cast<const u32x4 *>(sa.xw);
+  fa.nbp = g.nbp; fa.d_out = g.d_out; fa.d_out_pad = g.d_out_pad;
+  fa.steps = ta.steps; fa.grid = grid; fa.kp = g.kp;
   fa.scaled = grouped ? 1 : 0;
-  fa.has_weak = g.kp > 0 ? 1 : 0;
 
   const _Float16 *xp = static_cast<const _Float16 *>(x);
   _Float16 *yp = static_cast<_Float16 *>(y);
@@ -558,9 +570,9 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void 
     sa.x = xp + (size_t)t0 * g.d_in;
     sa.ntok = ntok;
     if (g.bits == 3)
-      hipLaunchKernelGGL(owq_tile_stage<3>, dim3((unsigned)sa.nchunk, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
+      hipLaunchKernelGGL(owq_tile_stage<3>, dim3((unsigned)g.nbp, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
     else
-      hipLaunchKernelGGL(owq_tile_stage<4>, dim3((unsigned)sa.nchunk, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
+      hipLaunchKernelGGL(owq_tile_stage<4>, dim3((unsigned)g.nbp, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
     hipLaunchKernelGGL(pick_mma(g.bits, nt, grouped), dim3((unsigned)grid, 1, 1), dim3(256, 1, 1),
                        2 * kUnitsPerTile * 16, st, ta);
     fa.y = yp + (size_t)t0 * g.d_out;
