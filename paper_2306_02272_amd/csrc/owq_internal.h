@@ -71,8 +71,10 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 
 // Tile path (defined in owq_tile.hip): three launches per pass of up to 64 tokens.
 // blob = DEVICE address of the packed blob; grid = workgroups of the main kernel.
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void *x, void *y,
+// waves = waves per workgroup of the main kernel (4 or 8).
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t waves, const void *x, void *y,
                 int32_t batch, void *stream);
+int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves);
 int device_lds_limit(int32_t *bytes);
 
 }  // namespace owq
@@ -85,4 +87,5 @@ struct owq_layer_s {
   void *dev_buf;
   int32_t lds_limit;
   int32_t tile_grid;     // workgroups of the tile kernel (tile layout only)
+  int32_t tile_waves;    // its waves per workgroup: 4 or 8
 };

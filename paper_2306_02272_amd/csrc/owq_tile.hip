@@ -26,6 +26,8 @@
 // No atomics: results are reproducible.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "owq_device.h"
 #include "owq_internal.h"
 
@@ -37,7 +39,6 @@ typedef float f4_t __attribute__((ext_vector_type(4)));
 typedef float f2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kUnitsPerTile = 2048;   // 16-byte units of one staged activation tile (256 columns x 64 tokens)
-constexpr int kSlotUnits = kTileSlotBytes / 16;
 
 // Bit offset o of pair i (columns 2i, 2i+1) of octet t of a block inside its 16-bit window;
 // the pair is OR-ed into 2^(10-o).  3-bit: the octet's place in its quad of 32 codes decides.
@@ -139,13 +140,12 @@ __global__ __launch_bounds__(256) void owq_tile_stage(const StageArgs a) {
     }
     a.bsum[(size_t)(2 * bp + b) * 64 + n] = (f2_t){sx, sb};
   }
-  if (bp == 0) {
-    for (int e = tid; e < 32 * a.kp; e += 256) {
-      const int ln = e / a.kp, t = e - ln * a.kp, nn = nt * 32 + ln;
-      if (nn < a.ntok) {
-        const int j = a.weak_idx[t];
-        a.xw[nn * a.kp + t] = j >= 0 ? a.x[(size_t)nn * a.d_in + j] : (_Float16)0;
-      }
+  // activations at the weak columns: the workgroups of a token tile share its 32 x kp elements
+  for (int e = bp * 256 + tid; e < 32 * a.kp; e += (int)gridDim.x * 256) {
+    const int ln = e / a.kp, t = e - ln * a.kp, nn = nt * 32 + ln;
+    if (nn < a.ntok) {
+      const int j = a.weak_idx[t];
+      a.xw[nn * a.kp + t] = j >= 0 ? a.x[(size_t)nn * a.d_in + j] : (_Float16)0;
     }
   }
 }
@@ -201,12 +201,18 @@ __device__ __forceinline__ f16_t mma(h8_t a, h8_t b, f16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-template <int BITS, int NT, bool GROUPED, int S>
+template <int S> struct KStep {};   // tag: k-step S of a column step
+template <int S> __device__ std::integral_constant<int, S> kstep_index(KStep<S>);
+
+// k-steps S..15 of one column step: wd0/wd1 = the dwords of the wave's two row tiles.
+// between(KStep<S>) runs after the matrix instructions of k-step S have been issued: the
+// caller spreads its global loads over the k-steps there, so that the memory pipeline of
+// the compute unit works on them while the matrix cores run.
+template <int BITS, int NT, int S>
 struct KSteps {
-  // k-steps S..15 of one column step: wd0/wd1 = the dwords of the wave's two row tiles
-  template <typename Epi>
+  template <typename Between>
   static __device__ __forceinline__ void run(const u32 *wd0, const u32 *wd1, const u32x4 *xb, int lane,
-                                             const Magic &M, f16_t *acc, Epi &epi) {
+                                             const Magic &M, f16_t *acc, Between &between) {
     const h8_t a0 = a_operand<BITS, S>(wd0, M), a1 = a_operand<BITS, S>(wd1, M);
     const h8_t b0 = __builtin_bit_cast(h8_t, xb[(S * 2 + 0) * 64 + lane]);
     acc[0] = mma(a0, b0, acc[0]);
@@ -216,42 +222,50 @@ struct KSteps {
       acc[1] = mma(a0, b1, acc[1]);
       acc[3] = mma(a1, b1, acc[3]);
     }
-    if (GROUPED && (S == 7 || S == 15)) epi(S >> 3);
-    KSteps<BITS, NT, GROUPED, S + 1>::run(wd0, wd1, xb, lane, M, acc, epi);
+    between(KStep<S>{});
+    KSteps<BITS, NT, S + 1>::run(wd0, wd1, xb, lane, M, acc, between);
   }
 };
-template <int BITS, int NT, bool GROUPED>
-struct KSteps<BITS, NT, GROUPED, 16> {
-  template <typename Epi>
-  static __device__ __forceinline__ void run(const u32 *, const u32 *, const u32x4 *, int, const Magic &, f16_t *, Epi &) {}
+template <int BITS, int NT>
+struct KSteps<BITS, NT, 16> {
+  template <typename Between>
+  static __device__ __forceinline__ void run(const u32 *, const u32 *, const u32x4 *, int, const Magic &, f16_t *, Between &) {}
 };
 
-// One workgroup = 4 waves = 256 rows (a row group); wave w owns row tiles 2w, 2w+1 of it.
-// Two workgroups share a compute unit (two waves per SIMD, at most 256 registers each) so that
-// one computes while the other waits at its barrier or for its loads.
-template <int BITS, int NT, bool GROUPED>
-__global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileArgs a) {
+template <int J> struct Slot {};   // tag: code buffer J of the three
+template <int J> __device__ std::integral_constant<int, J> slot_index(Slot<J>);
+
+// One workgroup = WAVES waves = WAVES*64 rows (a row group); wave w owns row tiles 2w, 2w+1
+// of it.  Two waves share a SIMD (two workgroups of 4 waves, or one of 8, per compute unit;
+// at most 256 registers each) so that one computes while the other waits at its barrier.
+template <int BITS, int NT, bool GROUPED, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(const TileArgs a) {
   constexpr int CH = BITS == 3 ? 3 : 4;
-  constexpr int XU = NT == 2 ? 8 : 4;           // activation units a thread stages per step
+  constexpr int THREADS = WAVES * 64;
+  constexpr int XU = (NT == 2 ? 2048 : 1024) / THREADS;   // activation units a thread stages per step
+  constexpr int RTG = 2 * WAVES;                           // row tiles per row group
+  constexpr int SLOT_UNITS = WAVES * 16 * 64;              // 16-byte units of one partial result
+  static_assert(XU >= 1 && XU <= 8 && 8 + 2 * CH <= 16, "loads must fit the 16 k-steps");
   extern __shared__ u32x4 lds[];                // two activation tiles
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int P = gridDim.x, p = blockIdx.x;
   const int lo = (int)((long long)p * a.steps / P), hi = (int)((long long)(p + 1) * a.steps / P);
   if (lo >= hi) return;
   int rg = lo / a.nbp, bp = lo - rg * a.nbp;    // the step being computed
+  int st = lo;
 
   // ---- fetch cursors: codes two steps ahead, activations one step ahead -------------
+  // Past the last step of the workgroup the cursors stay on it: the loads still go out
+  // (their number in flight is the same on every path) and their data is dropped.
   u32x4 cb[3][2][CH];
   int c_st = lo, c_rg = rg, c_bp = bp;
-  auto fetch_codes = [&](int slot) {
-#pragma unroll
-    for (int rtl = 0; rtl < 2; ++rtl) {
-      const int rt = min(c_rg * kTileGroupTiles + 2 * w + rtl, a.n_rt - 1);
-      const u32x4 *src = a.codes + ((size_t)(rt * a.nbp + c_bp) * CH) * 64 + lane;
-#pragma unroll
-      for (int c = 0; c < CH; ++c) cb[slot][rtl][c] = __builtin_nontemporal_load(src + c * 64);
-    }
-    if (c_st + 1 < hi) {                       // past the end: fetch the last step again
+  auto fetch_code = [&](int slot, int rtl, int c) {
+    const int rt = min(c_rg * RTG + 2 * w + rtl, a.n_rt - 1);
+    const u32x4 *src = a.codes + ((size_t)(rt * a.nbp + c_bp) * CH + c) * 64 + lane;
+    cb[slot][rtl][c] = __builtin_nontemporal_load(src);
+  };
+  auto advance_codes = [&]() {
+    if (c_st + 1 < hi) {
       ++c_st;
       if (++c_bp == a.nbp) { c_bp = 0; ++c_rg; }
     }
@@ -259,13 +273,11 @@ __global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileA
   u32x4 xg[XU];
   int x_st = lo, x_bp = bp;
   auto unit_of = [&](int j) {
-    const int i = tid + 256 * j;
+    const int i = tid + THREADS * j;
     return NT == 2 ? i : ((i >> 6) * 128 + (i & 63));
   };
-  auto fetch_x = [&]() {
-    const u32x4 *src = a.xs + (size_t)x_bp * kUnitsPerTile;
-#pragma unroll
-    for (int j = 0; j < XU; ++j) xg[j] = src[unit_of(j)];
+  auto fetch_x = [&](int j) { xg[j] = a.xs[(size_t)x_bp * kUnitsPerTile + unit_of(j)]; };
+  auto advance_x = [&]() {
     if (x_st + 1 < hi) {
       ++x_st;
       if (++x_bp == a.nbp) x_bp = 0;
@@ -276,16 +288,22 @@ __global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileA
     for (int j = 0; j < XU; ++j) lds[buf * kUnitsPerTile + unit_of(j)] = xg[j];
   };
 
-  fetch_x();
-  fetch_codes(0);
-  fetch_codes(1);
+#pragma unroll
+  for (int j = 0; j < XU; ++j) fetch_x(j);
+  advance_x();
+#pragma unroll
+  for (int sl = 0; sl < 2; ++sl) {
+#pragma unroll
+    for (int i = 0; i < 2 * CH; ++i) fetch_code(sl, i / CH, i % CH);
+    advance_codes();
+  }
   if (!GROUPED) {
     // While the first loads are in flight: the sums over all blocks of token n, for the
     // finish kernel (layers with one scale per row only).  Fixed order of additions.
-    __shared__ f2_t tred[4];
+    __shared__ f2_t tred[WAVES];
     for (int n = p; n < kScratchBatch; n += P) {
       float sx = 0.f, sb = 0.f;
-      for (int b = tid; b < a.nblk; b += 256) {
+      for (int b = tid; b < a.nblk; b += THREADS) {
         const f2_t v = a.bsum[(size_t)b * 64 + n];
         sx += v.x;
         sb += v.y;
@@ -298,8 +316,10 @@ __global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileA
       if (lane == 0) tred[w] = (f2_t){sx, sb};
       __syncthreads();
       if (tid == 0) {
-        const f2_t u0 = tred[0], u1 = tred[1], u2 = tred[2], u3 = tred[3];
-        a.tsum[n] = (f2_t){(u0.x + u1.x) + (u2.x + u3.x), (u0.y + u1.y) + (u2.y + u3.y)};
+        float tx = 0.f, tb = 0.f;
+#pragma unroll
+        for (int i = 0; i < WAVES; ++i) { tx += tred[i].x; tb += tred[i].y; }
+        a.tsum[n] = (f2_t){tx, tb};
       }
       __syncthreads();
     }
@@ -310,20 +330,18 @@ __global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileA
   Magic M;
   M.init();
   f16_t acc[4], tot[GROUPED ? 4 : 1];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  if (GROUPED) {
+  auto clear = [&](f16_t *v) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) tot[i][r] = 0.f;
-  }
+      for (int r = 0; r < 16; ++r) v[i][r] = 0.f;
+  };
+  clear(acc);
+  if constexpr (GROUPED) clear(tot);
   int gfirst = 2 * bp;                           // first block accumulated since acc was cleared
 
   auto flush = [&](const f16_t *v, int slot) {
-    f4_t *dst = a.slots + (size_t)slot * kSlotUnits + (w * 16) * 64 + lane;
+    f4_t *dst = a.slots + (size_t)slot * SLOT_UNITS + (w * 16) * 64 + lane;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (NT == 1 && (i & 1)) continue;
@@ -333,12 +351,6 @@ __global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileA
         dst[(i * 4 + q) * 64] = o;
       }
     }
-  };
-  auto clear = [&](f16_t *v) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) v[i][r] = 0.f;
   };
   // grouped scales: tot += s * (acc - sum c*x - z * sum x) over blocks b0..b1 of group g
   auto group_epilogue = [&](int g, int b0, int b1) {
@@ -355,7 +367,7 @@ __global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileA
     }
 #pragma unroll
     for (int rtl = 0; rtl < 2; ++rtl) {
-      const int rt = min(rg * kTileGroupTiles + 2 * w + rtl, a.n_rt - 1);
+      const int rt = min(rg * RTG + 2 * w + rtl, a.n_rt - 1);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = rt * kTileRows + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -373,46 +385,55 @@ __global__ __launch_bounds__(256, GROUPED ? 1 : 2) void owq_tile_mma(const TileA
   };
 
   int par = 0;
-  for (int st = lo; st < hi;) {
+  // One column step out of code buffer J: 16 k-steps on the matrix cores with the loads of
+  // the steps ahead spread between them, then the activations of the next step go to LDS.
+  auto step = [&](auto slot_tag) __attribute__((always_inline)) {
+    constexpr int J = decltype(slot_index(slot_tag))::value;
+    u32 wd0[CH * 4], wd1[CH * 4];
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      fetch_x();                     // activations of step st + 1
-      fetch_codes((j + 2) % 3);      // codes of step st + 2
-      if (st < hi) {
-        u32 wd0[CH * 4], wd1[CH * 4];
-#pragma unroll
-        for (int c = 0; c < CH; ++c) {
-          wd0[4 * c] = cb[j][0][c].x; wd0[4 * c + 1] = cb[j][0][c].y; wd0[4 * c + 2] = cb[j][0][c].z; wd0[4 * c + 3] = cb[j][0][c].w;
-          wd1[4 * c] = cb[j][1][c].x; wd1[4 * c + 1] = cb[j][1][c].y; wd1[4 * c + 2] = cb[j][1][c].z; wd1[4 * c + 3] = cb[j][1][c].w;
-        }
-        auto epi = [&](int half) {
-          const int blk = 2 * bp + half;
-          if ((blk + 1) % a.bpg == 0 || blk == a.nblk - 1) {
-            group_epilogue(blk / a.bpg, gfirst, blk);
-            gfirst = blk + 1;
-          }
-        };
-        KSteps<BITS, NT, GROUPED, 0>::run(wd0, wd1, lds + par * kUnitsPerTile, lane, M, acc, epi);
-        const bool last_of_group = bp == a.nbp - 1;
-        if (last_of_group || st == hi - 1) {
-          if constexpr (GROUPED) {
-            if (gfirst <= 2 * bp + 1) group_epilogue((2 * bp + 1) / a.bpg, gfirst, 2 * bp + 1);
-            flush(tot, p + rg);
-            clear(tot);
-          } else {
-            flush(acc, p + rg);
-            clear(acc);
-          }
-        }
-        if (last_of_group) { bp = 0; ++rg; } else { ++bp; }
-        if (last_of_group) gfirst = 0;
-      }
-      store_x(par ^ 1);
-      __syncthreads();
-      par ^= 1;
-      ++st;
+    for (int c = 0; c < CH; ++c) {
+      wd0[4 * c] = cb[J][0][c].x; wd0[4 * c + 1] = cb[J][0][c].y; wd0[4 * c + 2] = cb[J][0][c].z; wd0[4 * c + 3] = cb[J][0][c].w;
+      wd1[4 * c] = cb[J][1][c].x; wd1[4 * c + 1] = cb[J][1][c].y; wd1[4 * c + 2] = cb[J][1][c].z; wd1[4 * c + 3] = cb[J][1][c].w;
     }
+    auto between = [&](auto ks) __attribute__((always_inline)) {
+      constexpr int S = decltype(kstep_index(ks))::value;
+      if constexpr (S < XU) fetch_x(S);                       // activations of step st + 1
+      if constexpr (S == XU - 1) advance_x();
+      if constexpr (S >= 8 && S < 8 + 2 * CH) fetch_code((J + 2) % 3, (S - 8) / CH, (S - 8) % CH);   // codes of step st + 2
+      if constexpr (S == 8 + 2 * CH - 1) advance_codes();
+      if constexpr (GROUPED && (S == 7 || S == 15)) {
+        const int blk = 2 * bp + (S >> 3);
+        if ((blk + 1) % a.bpg == 0 || blk == a.nblk - 1) {
+          group_epilogue(blk / a.bpg, gfirst, blk);
+          gfirst = blk + 1;
+        }
+      }
+    };
+    KSteps<BITS, NT, 0>::run(wd0, wd1, lds + par * kUnitsPerTile, lane, M, acc, between);
+    const bool last_of_group = bp == a.nbp - 1;
+    if (last_of_group || st == hi - 1) {
+      if constexpr (GROUPED) {
+        if (gfirst <= 2 * bp + 1) group_epilogue((2 * bp + 1) / a.bpg, gfirst, 2 * bp + 1);
+        flush(tot, p + rg);
+        clear(tot);
+      } else {
+        flush(acc, p + rg);
+        clear(acc);
+      }
+    }
+    if (last_of_group) { bp = 0; ++rg; gfirst = 0; } else { ++bp; }
+    store_x(par ^ 1);
+    __syncthreads();
+    par ^= 1;
+    ++st;
+  };
+  while (st + 3 <= hi) {
+    step(Slot<0>{});
+    step(Slot<1>{});
+    step(Slot<2>{});
   }
+  if (st < hi) step(Slot<0>{});
+  if (st < hi) step(Slot<1>{});
 }
 
 // ---------------------------------------------------------------------------
@@ -426,16 +447,20 @@ struct FinishArgs {
   const u32x4 *xw;       // [64][kp/8] units
   _Float16 *y;           // [ntok][d_out] of this pass
   int nbp, d_out, d_out_pad, ntok, steps, grid, kp;
+  int waves;             // waves per workgroup of the main kernel: a slot holds waves*64 rows
   int scaled;            // the partial results are already scaled (grouped layers)
 };
 
-// grid = row groups x 4: one workgroup per 64 rows (the part of a slot one wave of the
-// main kernel wrote); wave i takes accumulator tile i = (row tile i >> 1, token tile i & 1).
+// grid = row groups x waves of the main kernel: one workgroup per 64 rows (the part of a slot
+// one wave of the main kernel wrote); wave i takes accumulator tile i = (row tile i >> 1,
+// token tile i & 1).
 __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
   __shared__ _Float16 out[64][72];     // [token][row], padded pitch
   const int tid = threadIdx.x, lane = tid & 63, i = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rg = blockIdx.x >> 2, w = blockIdx.x & 3;
+  const int rg = blockIdx.x / a.waves, w = blockIdx.x - rg * a.waves;
   const int nt = i & 1, rtl = i >> 1;
+  const int row_base = (rg * a.waves + w) * 64;
+  const size_t slot_units = (size_t)a.waves * 1024;
   const int ntiles = a.ntok > 32 ? 2 : 1;
   if (nt < ntiles) {
     const int n = nt * 32 + (lane & 31);
@@ -445,7 +470,7 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
     for (int r = 0; r < 16; ++r) wk[r] = 0.f;
     const int kunits = a.kp >> 3;
     if (kunits > 0) {
-      int row = rg * 256 + w * 64 + rtl * 32 + (lane & 31);
+      int row = row_base + rtl * 32 + (lane & 31);
       if (row > a.d_out_pad - 1) row = a.d_out_pad - 1;
       const u32x4 *wsrc = a.weak_w + (size_t)row * kunits, *xsrc = a.xw + (size_t)n * kunits;
       const int kg = lane >> 5;
@@ -479,7 +504,7 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int pc = p + j <= p_last ? p + j : p_last;
-          v[j] = a.slots[(size_t)(pc + rg) * kSlotUnits + unit];
+          v[j] = a.slots[(size_t)(pc + rg) * slot_units + unit];
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -487,7 +512,7 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
       }
       const int r0 = rtl * 32 + 8 * q + 4 * (lane >> 5);      // row within the workgroup's 64
       if (!a.scaled) {
-        int row = rg * 256 + w * 64 + r0;
+        int row = row_base + r0;
         if (row > a.d_out_pad - 4) row = a.d_out_pad - 4;
         const u32x4 szw = *reinterpret_cast<const u32x4 *>(a.sz + row);
         const u32 s4[4] = {szw.x, szw.y, szw.z, szw.w};
@@ -503,7 +528,6 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
     }
   }
   __syncthreads();
-  const int row_base = rg * 256 + w * 64;
   for (int e = tid; e < a.ntok * 64; e += 256) {
     const int n = e >> 6, r = e & 63;
     if (row_base + r < a.d_out) a.y[(size_t)n * a.d_out + row_base + r] = out[n][r];
@@ -515,23 +539,40 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
 // ---------------------------------------------------------------------------
 typedef void (*mma_fn)(const TileArgs);
 
-static mma_fn pick_mma(int bits, int nt, bool grouped) {
-  if (bits == 3) {
-    if (nt == 2) return grouped ? owq_tile_mma<3, 2, true> : owq_tile_mma<3, 2, false>;
-    return grouped ? owq_tile_mma<3, 1, true> : owq_tile_mma<3, 1, false>;
-  }
-  if (nt == 2) return grouped ? owq_tile_mma<4, 2, true> : owq_tile_mma<4, 2, false>;
-  return grouped ? owq_tile_mma<4, 1, true> : owq_tile_mma<4, 1, false>;
+template <int BITS, int WAVES>
+static mma_fn pick_mma2(int nt, bool grouped) {
+  if (nt == 2) return grouped ? owq_tile_mma<BITS, 2, true, WAVES> : owq_tile_mma<BITS, 2, false, WAVES>;
+  return grouped ? owq_tile_mma<BITS, 1, true, WAVES> : owq_tile_mma<BITS, 1, false, WAVES>;
 }
 
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void *x, void *y,
+static mma_fn pick_mma(int bits, int nt, bool grouped, int waves) {
+  if (bits == 3) return waves == 8 ? pick_mma2<3, 8>(nt, grouped) : pick_mma2<3, 4>(nt, grouped);
+  return waves == 8 ? pick_mma2<4, 8>(nt, grouped) : pick_mma2<4, 4>(nt, grouped);
+}
+
+// Most workgroups the partial-result slots of the scratch area allow for `waves` per workgroup.
+int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves) {
+  const TileScratch ts = tile_scratch(g);
+  const int64_t slot = (int64_t)waves * 16384;
+  const int64_t n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
+  const int64_t room = (int64_t)(ts.total - ts.off_slots) / slot - n_rg;
+  const int64_t steps = n_rg * g.nbp;
+  int64_t lim = room < steps ? room : steps;
+  const int64_t cap = waves == 8 ? kTileGridMax / 2 : kTileGridMax;
+  if (lim > cap) lim = cap;
+  return lim < 0 ? 0 : (int32_t)lim;
+}
+
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t waves, const void *x, void *y,
                 int32_t batch, void *stream) {
   const TileScratch ts = tile_scratch(g);
   uint8_t *base = static_cast<uint8_t *>(blob);
   uint8_t *scr = base + g.off_scratch;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool grouped = g.n_groups > 1;
-  if (grid < 1 || grid > ts.grid_max) return (int)hipErrorInvalidValue;
+  if (waves != 4 && waves != 8) return (int)hipErrorInvalidValue;
+  if (grid < 1 || grid > tile_grid_limit(g, waves)) return (int)hipErrorInvalidValue;
+  const int n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
 
   StageArgs sa;
   sa.wmask = base + g.off_wmask;
@@ -550,7 +591,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void 
   ta.slots = reinterpret_cast<f4_t *>(scr + ts.off_slots);
   ta.nbp = g.nbp; ta.n_rt = g.n_rt; ta.n_groups = g.n_groups; ta.nblk = g.nblk;
   ta.bpg = g.group_size ? g.group_size / kBlockCols : g.nblk;
-  ta.steps = ts.n_rg * g.nbp;
+  ta.steps = n_rg * g.nbp;
 
   FinishArgs fa;
   fa.slots = ta.slots;
@@ -559,7 +600,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void 
   fa.weak_w = reinterpret_cast<const u32x4 *>(base + g.off_weak_w);
   fa.xw = reinterpret_cast<const u32x4 *>(sa.xw);
   fa.nbp = g.nbp; fa.d_out = g.d_out; fa.d_out_pad = g.d_out_pad;
-  fa.steps = ta.steps; fa.grid = grid; fa.kp = g.kp;
+  fa.steps = ta.steps; fa.grid = grid; fa.kp = g.kp; fa.waves = waves;
   fa.scaled = grouped ? 1 : 0;
 
   const _Float16 *xp = static_cast<const _Float16 *>(x);
@@ -573,11 +614,11 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, const void 
       hipLaunchKernelGGL(owq_tile_stage<3>, dim3((unsigned)g.nbp, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
     else
       hipLaunchKernelGGL(owq_tile_stage<4>, dim3((unsigned)g.nbp, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
-    hipLaunchKernelGGL(pick_mma(g.bits, nt, grouped), dim3((unsigned)grid, 1, 1), dim3(256, 1, 1),
+    hipLaunchKernelGGL(pick_mma(g.bits, nt, grouped, waves), dim3((unsigned)grid, 1, 1), dim3((unsigned)(waves * 64), 1, 1),
                        2 * kUnitsPerTile * 16, st, ta);
     fa.y = yp + (size_t)t0 * g.d_out;
     fa.ntok = ntok;
-    hipLaunchKernelGGL(owq_tile_finish, dim3((unsigned)(ts.n_rg * 4), 1, 1), dim3(256, 1, 1), 0, st, fa);
+    hipLaunchKernelGGL(owq_tile_finish, dim3((unsigned)(n_rg * waves), 1, 1), dim3(256, 1, 1), 0, st, fa);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
