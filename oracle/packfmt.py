@@ -49,7 +49,8 @@ with these differences:
     256*bp + 128*b + 16*t + 8*kg + e.  The 128 lane columns are packed into the
     lane's dwords exactly as the 128 columns of a block are in layout 0.
     Tiles are ordered [row tile][block pair]; a tile is [chunk][lane][16 bytes].
-  * sz and weak_w have n_rt*32 rows.
+  * sz and weak_w have n_rt*32 rows; sz is stored group-major, [G][n_rt*32] dwords (the
+    rows of a tile next to each other).
   * two more sections follow weak_idx: wmask, one byte per 8 input columns
     (bit e = column 8i+e is weak), nbp*32 bytes; and a scratch area the library
     uses at run time (contents undefined, zero in a fresh blob) of
@@ -219,6 +220,8 @@ def pack_layer(codes, scale, zero, group_size, weak_idx, weak_w, bits, layout: i
     assert s_bits.shape == (d_out, geo.n_groups) and z_bits.shape == (d_out, geo.n_groups)
     sz = np.zeros((geo.d_out_pad, geo.n_groups), dtype=np.uint32)
     sz[:d_out] = s_bits | (z_bits << np.uint32(16))
+    if geo.layout == 1:
+        sz = np.ascontiguousarray(sz.T)               # group-major
     b = sz.astype("<u4").view(np.uint8).reshape(-1)
     blob[geo.off_sz:geo.off_sz + b.size] = b
 
@@ -301,7 +304,10 @@ def unpack_params(blob: np.ndarray, geo: Geometry):
     """(scale fp16 [d_out,G], zero fp16 [d_out,G], weak_idx int32 [k], weak_w fp16 [d_out,k])."""
     raw = np.asarray(blob, dtype=np.uint8).tobytes()
     sz = np.frombuffer(raw, dtype="<u4", count=geo.d_out_pad * geo.n_groups, offset=geo.off_sz)
-    sz = sz.reshape(geo.d_out_pad, geo.n_groups)[:geo.d_out]
+    if geo.layout == 1:
+        sz = sz.reshape(geo.n_groups, geo.d_out_pad).T[:geo.d_out]
+    else:
+        sz = sz.reshape(geo.d_out_pad, geo.n_groups)[:geo.d_out]
     scale = (sz & 0xFFFF).astype(np.uint16).view(np.float16)
     zero = (sz >> 16).astype(np.uint16).view(np.float16)
     ww = np.frombuffer(raw, dtype=np.float16, count=geo.d_out_pad * geo.kp, offset=geo.off_weak_w)

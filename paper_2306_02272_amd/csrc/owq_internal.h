@@ -75,6 +75,7 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t waves, const void *x, void *y,
                 int32_t batch, void *stream);
 int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves);
+int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit);   // LDS opt-in for grouped layers
 int device_lds_limit(int32_t *bytes);
 
 }  // namespace owq

@@ -194,9 +194,15 @@ void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *ou
     }
   }
 
+  // single-token layout: [row][group]; tile layout: [group][row], so that the rows of a tile
+  // are contiguous
   uint32_t *sz = reinterpret_cast<uint32_t *>(out + g.off_sz);
-  for (int64_t i = 0; i < (int64_t)g.d_out * g.n_groups; ++i)
-    sz[i] = (uint32_t)d->scale[i] | ((uint32_t)d->zero[i] << 16);
+  for (int64_t i = 0; i < g.d_out; ++i)
+    for (int32_t gr = 0; gr < g.n_groups; ++gr) {
+      const int64_t src = i * g.n_groups + gr;
+      const int64_t dst = g.layout == OWQ_LAYOUT_TILE ? (int64_t)gr * g.d_out_pad + i : src;
+      sz[dst] = (uint32_t)d->scale[src] | ((uint32_t)d->zero[src] << 16);
+    }
 
   uint16_t *ww = reinterpret_cast<uint16_t *>(out + g.off_weak_w);
   for (int64_t i = 0; i < g.d_out; ++i)

@@ -155,12 +155,12 @@ __global__ __launch_bounds__(256) void owq_tile_stage(const StageArgs a) {
 // ---------------------------------------------------------------------------
 struct TileArgs {
   const u32x4 *codes;
-  const u32 *sz;
+  const u32 *sz;         // [n_groups][d_out_pad]: fp16 scale | fp16 zero << 16
   const u32x4 *xs;
   const f2_t *bsum;
   f2_t *tsum;            // [64]: per token, sum over all blocks of (x, c*x)
   f4_t *slots;
-  int nbp, n_rt, n_groups, bpg, nblk;
+  int nbp, n_rt, n_groups, bpg, nblk, d_out_pad;
   int steps;             // row groups x column steps
 };
 
@@ -245,8 +245,14 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
   constexpr int XU = (NT == 2 ? 2048 : 1024) / THREADS;   // activation units a thread stages per step
   constexpr int RTG = 2 * WAVES;                           // row tiles per row group
   constexpr int SLOT_UNITS = WAVES * 16 * 64;              // 16-byte units of one partial result
+  constexpr int ROWS = WAVES * 64;
+  // LDS buffer of a step: the activation tile; for grouped layers also (scale, zero) as two
+  // floats per row and block of the step, and (sum x, sum c*x) per token and block
+  constexpr int SZ_UNITS = GROUPED ? ROWS : 0, BS_UNITS = GROUPED ? 64 : 0;
+  constexpr int BUF_UNITS = kUnitsPerTile + SZ_UNITS + BS_UNITS;
   static_assert(XU >= 1 && XU <= 8 && 8 + 2 * CH <= 16, "loads must fit the 16 k-steps");
-  extern __shared__ u32x4 lds[];                // two activation tiles
+  static_assert(THREADS >= ROWS / 2 + 64, "one thread per staged unit of scales and sums");
+  extern __shared__ u32x4 lds[];                // two buffers
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int P = gridDim.x, p = blockIdx.x;
   const int lo = (int)((long long)p * a.steps / P), hi = (int)((long long)(p + 1) * a.steps / P);
@@ -271,25 +277,58 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
     }
   };
   u32x4 xg[XU];
-  int x_st = lo, x_bp = bp;
+  u32x4 auxg = {0u, 0u, 0u, 0u};
+  int x_st = lo, x_bp = bp, x_rg = rg;
   auto unit_of = [&](int j) {
     const int i = tid + THREADS * j;
     return NT == 2 ? i : ((i >> 6) * 128 + (i & 63));
   };
   auto fetch_x = [&](int j) { xg[j] = a.xs[(size_t)x_bp * kUnitsPerTile + unit_of(j)]; };
+  // grouped layers: thread t < ROWS/2 stages (scale, zero) of 4 rows of one block of the step,
+  // the next 64 threads stage the sums of 2 tokens of one block
+  auto fetch_aux = [&]() {
+    if constexpr (GROUPED) {
+      const u32x4 *src = reinterpret_cast<const u32x4 *>(a.sz);
+      if (tid < ROWS / 2) {
+        const int h = tid / (ROWS / 4), r4 = tid - h * (ROWS / 4);
+        int g = (2 * x_bp + h) / a.bpg;
+        if (g > a.n_groups - 1) g = a.n_groups - 1;
+        int row = x_rg * ROWS + r4 * 4;
+        if (row > a.d_out_pad - 4) row = a.d_out_pad - 4;
+        src = reinterpret_cast<const u32x4 *>(a.sz + (size_t)g * a.d_out_pad + row);
+      } else if (tid < ROWS / 2 + 64) {
+        const int u = tid - ROWS / 2;
+        src = reinterpret_cast<const u32x4 *>(a.bsum + (size_t)(2 * x_bp + (u >> 5)) * 64 + (u & 31) * 2);
+      }
+      auxg = *src;
+    }
+  };
   auto advance_x = [&]() {
     if (x_st + 1 < hi) {
       ++x_st;
-      if (++x_bp == a.nbp) x_bp = 0;
+      if (++x_bp == a.nbp) { x_bp = 0; ++x_rg; }
     }
   };
   auto store_x = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < XU; ++j) lds[buf * kUnitsPerTile + unit_of(j)] = xg[j];
+    for (int j = 0; j < XU; ++j) lds[buf * BUF_UNITS + unit_of(j)] = xg[j];
+    if constexpr (GROUPED) {
+      if (tid < ROWS / 2) {
+        const u32 d[4] = {auxg.x, auxg.y, auxg.z, auxg.w};
+        f4_t lo4 = {half_lo(d[0]), half_hi(d[0]), half_lo(d[1]), half_hi(d[1])};
+        f4_t hi4 = {half_lo(d[2]), half_hi(d[2]), half_lo(d[3]), half_hi(d[3])};
+        f4_t *dst = reinterpret_cast<f4_t *>(lds + buf * BUF_UNITS + kUnitsPerTile) + tid * 2;
+        dst[0] = lo4;
+        dst[1] = hi4;
+      } else if (tid < ROWS / 2 + 64) {
+        lds[buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS + (tid - ROWS / 2)] = auxg;
+      }
+    }
   };
 
 #pragma unroll
   for (int j = 0; j < XU; ++j) fetch_x(j);
+  fetch_aux();
   advance_x();
 #pragma unroll
   for (int sl = 0; sl < 2; ++sl) {
@@ -338,8 +377,6 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
   };
   clear(acc);
   if constexpr (GROUPED) clear(tot);
-  int gfirst = 2 * bp;                           // first block accumulated since acc was cleared
-
   auto flush = [&](const f16_t *v, int slot) {
     f4_t *dst = a.slots + (size_t)slot * SLOT_UNITS + (w * 16) * 64 + lane;
 #pragma unroll
@@ -352,36 +389,36 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
       }
     }
   };
-  // grouped scales: tot += s * (acc - sum c*x - z * sum x) over blocks b0..b1 of group g
-  auto group_epilogue = [&](int g, int b0, int b1) {
-    if (g > a.n_groups - 1) g = a.n_groups - 1;
+  // grouped layers, after the 8 k-steps of block h of the step:
+  // tot += s * (acc - sum c*x - z * sum x) with the block's staged scales and sums; acc = 0
+  auto block_epilogue = [&](int h, int buf) __attribute__((always_inline)) {
+    const float *szl = reinterpret_cast<const float *>(lds + buf * BUF_UNITS + kUnitsPerTile);
+    const f2_t *bsl = reinterpret_cast<const f2_t *>(lds + buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS);
     float X[2] = {0.f, 0.f}, Bc[2] = {0.f, 0.f};
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const f2_t *src = a.bsum + nt * 32 + (lane & 31);
-      for (int b = b0; b <= b1; ++b) {
-        const f2_t v = src[(size_t)b * 64];
-        X[nt] += v.x;
-        Bc[nt] += v.y;
-      }
+      const f2_t v = bsl[h * 64 + nt * 32 + (lane & 31)];
+      X[nt] = v.x;
+      Bc[nt] = v.y;
     }
 #pragma unroll
-    for (int rtl = 0; rtl < 2; ++rtl) {
-      const int rt = min(rg * RTG + 2 * w + rtl, a.n_rt - 1);
+    for (int rtl = 0; rtl < 2; ++rtl)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = rt * kTileRows + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const u32 szw = a.sz[(size_t)row * a.n_groups + g];
-        const float sc = half_lo(szw), zp = half_hi(szw);
+      for (int q = 0; q < 4; ++q) {
+        const f4_t *src = reinterpret_cast<const f4_t *>(szl + (size_t)(h * ROWS + w * 64 + rtl * 32 + 8 * q + 4 * (lane >> 5)) * 2);
+        const f4_t s01 = src[0], s23 = src[1];
+        const float sc[4] = {s01[0], s01[2], s23[0], s23[2]}, zp[4] = {s01[1], s01[3], s23[1], s23[3]};
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          float v = acc[rtl * 2 + nt][r] - Bc[nt];
-          v = __builtin_fmaf(-zp, X[nt], v);
-          tot[GROUPED ? rtl * 2 + nt : 0][r] = __builtin_fmaf(sc, v, tot[GROUPED ? rtl * 2 + nt : 0][r]);
-          acc[rtl * 2 + nt][r] = 0.f;
-        }
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            constexpr int kTot = GROUPED ? 1 : 0;
+            float v = acc[rtl * 2 + nt][4 * q + e] - Bc[nt];
+            v = __builtin_fmaf(-zp[e], X[nt], v);
+            tot[kTot * (rtl * 2 + nt)][4 * q + e] = __builtin_fmaf(sc[e], v, tot[kTot * (rtl * 2 + nt)][4 * q + e]);
+            acc[rtl * 2 + nt][4 * q + e] = 0.f;
+          }
       }
-    }
   };
 
   int par = 0;
@@ -398,22 +435,15 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
     auto between = [&](auto ks) __attribute__((always_inline)) {
       constexpr int S = decltype(kstep_index(ks))::value;
       if constexpr (S < XU) fetch_x(S);                       // activations of step st + 1
-      if constexpr (S == XU - 1) advance_x();
       if constexpr (S >= 8 && S < 8 + 2 * CH) fetch_code((J + 2) % 3, (S - 8) / CH, (S - 8) % CH);   // codes of step st + 2
       if constexpr (S == 8 + 2 * CH - 1) advance_codes();
-      if constexpr (GROUPED && (S == 7 || S == 15)) {
-        const int blk = 2 * bp + (S >> 3);
-        if ((blk + 1) % a.bpg == 0 || blk == a.nblk - 1) {
-          group_epilogue(blk / a.bpg, gfirst, blk);
-          gfirst = blk + 1;
-        }
-      }
+      if constexpr (S == XU - 1) { fetch_aux(); advance_x(); }
+      if constexpr (GROUPED && (S == 7 || S == 15)) block_epilogue(S >> 3, par);
     };
-    KSteps<BITS, NT, 0>::run(wd0, wd1, lds + par * kUnitsPerTile, lane, M, acc, between);
+    KSteps<BITS, NT, 0>::run(wd0, wd1, lds + par * BUF_UNITS, lane, M, acc, between);
     const bool last_of_group = bp == a.nbp - 1;
     if (last_of_group || st == hi - 1) {
       if constexpr (GROUPED) {
-        if (gfirst <= 2 * bp + 1) group_epilogue((2 * bp + 1) / a.bpg, gfirst, 2 * bp + 1);
         flush(tot, p + rg);
         clear(tot);
       } else {
@@ -421,7 +451,7 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
         clear(acc);
       }
     }
-    if (last_of_group) { bp = 0; ++rg; gfirst = 0; } else { ++bp; }
+    if (last_of_group) { bp = 0; ++rg; } else { ++bp; }
     store_x(par ^ 1);
     __syncthreads();
     par ^= 1;
@@ -550,6 +580,26 @@ static mma_fn pick_mma(int bits, int nt, bool grouped, int waves) {
   return waves == 8 ? pick_mma2<4, 8>(nt, grouped) : pick_mma2<4, 4>(nt, grouped);
 }
 
+static int32_t tile_lds_bytes(bool grouped, int waves) {
+  return 2 * (kUnitsPerTile + (grouped ? waves * 64 + 64 : 0)) * 16;
+}
+
+// Grouped layers stage scales and sums next to the activations: more than the 64 KiB of LDS a
+// kernel may use without asking.  Returns a hipError_t as int.
+int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit) {
+  if (g.n_groups <= 1) return (int)hipSuccess;
+  for (int waves = 4; waves <= 8; waves += 4) {
+    const int32_t need = tile_lds_bytes(true, waves);
+    if (need > lds_limit) return (int)hipErrorInvalidValue;
+    for (int nt = 1; nt <= 2; ++nt) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_mma(g.bits, nt, true, waves)),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, need);
+      if (e != hipSuccess) return (int)e;
+    }
+  }
+  return (int)hipSuccess;
+}
+
 // Most workgroups the partial-result slots of the scratch area allow for `waves` per workgroup.
 int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves) {
   const TileScratch ts = tile_scratch(g);
@@ -589,7 +639,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t wav
   ta.bsum = sa.bsum;
   ta.tsum = reinterpret_cast<f2_t *>(scr + ts.off_tsum);
   ta.slots = reinterpret_cast<f4_t *>(scr + ts.off_slots);
-  ta.nbp = g.nbp; ta.n_rt = g.n_rt; ta.n_groups = g.n_groups; ta.nblk = g.nblk;
+  ta.nbp = g.nbp; ta.n_rt = g.n_rt; ta.n_groups = g.n_groups; ta.nblk = g.nblk; ta.d_out_pad = g.d_out_pad;
   ta.bpg = g.group_size ? g.group_size / kBlockCols : g.nblk;
   ta.steps = n_rg * g.nbp;
 
@@ -615,7 +665,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t wav
     else
       hipLaunchKernelGGL(owq_tile_stage<4>, dim3((unsigned)g.nbp, (unsigned)nt, 1), dim3(256, 1, 1), 0, st, sa);
     hipLaunchKernelGGL(pick_mma(g.bits, nt, grouped, waves), dim3((unsigned)grid, 1, 1), dim3((unsigned)(waves * 64), 1, 1),
-                       2 * kUnitsPerTile * 16, st, ta);
+                       tile_lds_bytes(grouped, waves), st, ta);
     fa.y = yp + (size_t)t0 * g.d_out;
     fa.ntok = ntok;
     hipLaunchKernelGGL(owq_tile_finish, dim3((unsigned)(n_rg * waves), 1, 1), dim3(256, 1, 1), 0, st, fa);

@@ -78,6 +78,12 @@ def test_tile_layout_blob_sections():
     np.testing.assert_array_equal(ix, L.weak_idx)
     np.testing.assert_array_equal(ww.view(np.uint16), L.weak_w.view(np.uint16))
     np.testing.assert_array_equal(s.view(np.uint16), L.scale.view(np.uint16))
+    np.testing.assert_array_equal(z.view(np.uint16), L.zero.view(np.uint16))
+    # group-major: the dword of (row 7, group 2) sits at off_sz + (2 * d_out_pad + 7) * 4
+    assert geo.d_out_pad == 64 and geo.n_groups == 3
+    at = geo.off_sz + (2 * 64 + 7) * 4
+    want = int(L.scale.view(np.uint16)[7, 2]) | (int(L.zero.view(np.uint16)[7, 2]) << 16)
+    assert int.from_bytes(blob[at:at + 4].tobytes(), "little") == want
     mask = np.unpackbits(blob[geo.off_wmask:geo.off_wmask + geo.nbp * 32], bitorder="little")
     assert np.flatnonzero(mask).tolist() == L.weak_idx.tolist()
     assert not blob[geo.off_scratch:].any()
