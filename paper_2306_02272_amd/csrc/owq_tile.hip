@@ -486,81 +486,101 @@ struct FinishArgs {
 // token tile i & 1).
 __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
   __shared__ _Float16 out[64][72];     // [token][row], padded pitch
-  const int tid = threadIdx.x, lane = tid & 63, i = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rg = blockIdx.x / a.waves, w = blockIdx.x - rg * a.waves;
-  const int nt = i & 1, rtl = i >> 1;
   const int row_base = (rg * a.waves + w) * 64;
   const size_t slot_units = (size_t)a.waves * 1024;
-  const int ntiles = a.ntok > 32 ? 2 : 1;
-  if (nt < ntiles) {
-    const int n = nt * 32 + (lane & 31);
-    // product of the fp16 weak columns with the activations gathered at their indices
-    f16_t wk;
+  // 64 tokens: wave = accumulator tile (row tile wv >> 1, token tile wv & 1), all four groups
+  // of 8 rows; 32 tokens or fewer: two waves share a row tile, two groups of 8 rows each
+  const bool two = a.ntok > 32;
+  const int i = two ? wv : (wv >> 1) * 2, nt = i & 1, rtl = i >> 1;
+  const int q0 = two ? 0 : 2 * (wv & 1), qn = two ? 4 : 2;
+  const int n = nt * 32 + (lane & 31);
+  // product of the fp16 weak columns with the activations gathered at their indices
+  f16_t wk;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) wk[r] = 0.f;
-    const int kunits = a.kp >> 3;
-    if (kunits > 0) {
-      int row = row_base + rtl * 32 + (lane & 31);
-      if (row > a.d_out_pad - 1) row = a.d_out_pad - 1;
-      const u32x4 *wsrc = a.weak_w + (size_t)row * kunits, *xsrc = a.xw + (size_t)n * kunits;
-      const int kg = lane >> 5;
-      for (int s0 = 0; 2 * s0 < kunits; s0 += 4) {
-        u32x4 av[4], bv[4];
+  for (int r = 0; r < 16; ++r) wk[r] = 0.f;
+  const int kunits = a.kp >> 3;
+  if (kunits > 0) {
+    int row = row_base + rtl * 32 + (lane & 31);
+    if (row > a.d_out_pad - 1) row = a.d_out_pad - 1;
+    const u32x4 *wsrc = a.weak_w + (size_t)row * kunits, *xsrc = a.xw + (size_t)n * kunits;
+    const int kg = lane >> 5;
+    for (int s0 = 0; 2 * s0 < kunits; s0 += 4) {
+      u32x4 av[4], bv[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {      // four K-steps of loads in flight
-          const int u = 2 * (s0 + j) + kg;
-          const bool live = u < kunits;
-          const int uc = live ? u : 0;
-          av[j] = wsrc[uc];
-          bv[j] = xsrc[uc];
-          if (!live) av[j] = (u32x4){0u, 0u, 0u, 0u};
-          if (!live) bv[j] = (u32x4){0u, 0u, 0u, 0u};
-        }
+      for (int j = 0; j < 4; ++j) {      // four K-steps of loads in flight
+        const int u = 2 * (s0 + j) + kg;
+        const bool live = u < kunits;
+        const int uc = live ? u : 0;
+        av[j] = wsrc[uc];
+        bv[j] = xsrc[uc];
+        if (!live) av[j] = (u32x4){0u, 0u, 0u, 0u};
+        if (!live) bv[j] = (u32x4){0u, 0u, 0u, 0u};
+      }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wk = mma(__builtin_bit_cast(h8_t, av[j]), __builtin_bit_cast(h8_t, bv[j]), wk);
+      for (int j = 0; j < 4; ++j) wk = mma(__builtin_bit_cast(h8_t, av[j]), __builtin_bit_cast(h8_t, bv[j]), wk);
+    }
+  }
+  // owners of the first and the last step of this row group
+  const long long st0 = (long long)rg * a.nbp, st1 = st0 + a.nbp - 1;
+  const int p_first = (int)(((st0 + 1) * a.grid - 1) / a.steps), p_last = (int)(((st1 + 1) * a.grid - 1) / a.steps);
+  f2_t t = {0.f, 0.f};
+  if (!a.scaled) t = a.tsum[n];
+  f4_t sum[4];
+#pragma unroll
+  for (int qq = 0; qq < 4; ++qq) sum[qq] = (f4_t){0.f, 0.f, 0.f, 0.f};
+  const f4_t *src = a.slots + (size_t)((w * 4 + i) * 4 + q0) * 64 + lane;
+  constexpr int kInFlight = 4;                       // partial results fetched together (x up to 4 row groups)
+  for (int p = p_first; p <= p_last; p += kInFlight) {     // fixed order of additions
+    f4_t v[kInFlight][4];
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j) {
+      if (p + j > p_last) continue;                 // same for the whole workgroup
+#pragma unroll
+      for (int qq = 0; qq < 4; ++qq)
+        if (qq < qn) v[j][qq] = src[(size_t)(p + j + rg) * slot_units + qq * 64];
+    }
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j)
+      if (p + j <= p_last) {
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq)
+          if (qq < qn) sum[qq] += v[j][qq];
+      }
+  }
+#pragma unroll
+  for (int qq = 0; qq < 4; ++qq) {
+    if (qq >= qn) continue;
+    const int q = q0 + qq;
+    const int r0 = rtl * 32 + 8 * q + 4 * (lane >> 5);      // row within the workgroup's 64
+    f4_t sm = sum[qq];
+    if (!a.scaled) {
+      int row = row_base + r0;
+      if (row > a.d_out_pad - 4) row = a.d_out_pad - 4;
+      const u32x4 szw = *reinterpret_cast<const u32x4 *>(a.sz + row);
+      const u32 s4[4] = {szw.x, szw.y, szw.z, szw.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float v = sm[e] - t.y;
+        v = __builtin_fmaf(-half_hi(s4[e]), t.x, v);
+        sm[e] = v * half_lo(s4[e]);
       }
     }
-    // owners of the first and the last step of this row group
-    const long long st0 = (long long)rg * a.nbp, st1 = st0 + a.nbp - 1;
-    const int p_first = (int)(((st0 + 1) * a.grid - 1) / a.steps), p_last = (int)(((st1 + 1) * a.grid - 1) / a.steps);
-    f2_t t = {0.f, 0.f};
-    if (!a.scaled) t = a.tsum[n];
+    // wk[4q + e] with q known only at run time: pick by comparison, no indexed register file access
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const size_t unit = (size_t)((w * 4 + i) * 4 + q) * 64 + lane;
-      f4_t sum = {0.f, 0.f, 0.f, 0.f};
-      for (int p = p_first; p <= p_last; p += 4) {   // fixed order of additions, four loads in flight
-        f4_t v[4];
+    for (int e = 0; e < 4; ++e) {
+      float wv4 = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int pc = p + j <= p_last ? p + j : p_last;
-          v[j] = a.slots[(size_t)(pc + rg) * slot_units + unit];
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (p + j <= p_last) sum += v[j];
-      }
-      const int r0 = rtl * 32 + 8 * q + 4 * (lane >> 5);      // row within the workgroup's 64
-      if (!a.scaled) {
-        int row = row_base + r0;
-        if (row > a.d_out_pad - 4) row = a.d_out_pad - 4;
-        const u32x4 szw = *reinterpret_cast<const u32x4 *>(a.sz + row);
-        const u32 s4[4] = {szw.x, szw.y, szw.z, szw.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float v = sum[e] - t.y;
-          v = __builtin_fmaf(-half_hi(s4[e]), t.x, v);
-          sum[e] = v * half_lo(s4[e]);
-        }
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) out[n][r0 + e] = (_Float16)(sum[e] + wk[4 * q + e]);
+      for (int qs = 0; qs < 4; ++qs)
+        if (qs == q) wv4 = wk[4 * qs + e];
+      out[n][r0 + e] = (_Float16)(sm[e] + wv4);
     }
   }
   __syncthreads();
   for (int e = tid; e < a.ntok * 64; e += 256) {
-    const int n = e >> 6, r = e & 63;
-    if (row_base + r < a.d_out) a.y[(size_t)n * a.d_out + row_base + r] = out[n][r];
+    const int nn = e >> 6, r = e & 63;
+    if (row_base + r < a.d_out) a.y[(size_t)nn * a.d_out + row_base + r] = out[nn][r];
   }
 }
 
