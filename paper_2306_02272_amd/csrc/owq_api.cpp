@@ -92,6 +92,8 @@ static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_ha
     if (lds_limit < 65536) return OWQ_ERR_UNSUPPORTED;
     tile_grid = tile_grid_limit(g, tile_waves);
     if (tile_grid < 1) return OWQ_ERR_UNSUPPORTED;
+    // grouped layers keep more state per wave: one workgroup per compute unit at a time
+    if (g.n_groups > 1 && tile_grid > kTileGridMax / 2) tile_grid = kTileGridMax / 2;
     const int e = prepare_tile_kernels(g, lds_limit);
     if (e == (int)hipErrorInvalidValue) return OWQ_ERR_UNSUPPORTED;
     if (e != 0) return OWQ_ERR_HIP;
