@@ -373,31 +373,54 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   TRACE(7);
 
   // ---- (5) add the partials of each row; weak chunks beyond one per block -------
+  // A group of 16 lanes takes up to four rows at a time: their LDS reads go out together
+  // and the four reductions overlap.  Reads past the end of a row are clamped and dropped by
+  // select.
   const int rows_here = (rt_end - rt0) * a.r;
-  const int l16 = tid & 15;
-  for (int rs = tid >> 4; rs < rows_here; rs += nthr >> 4) {
-    const int row = rt0 * a.r + rs;
-    const float *pr = part + rs * a.ppitch;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    for (int b = l16; b < a.nblk; b += 64) {              // four independent LDS reads per trip
-      s0 += pr[b];
-      s1 += (b + 16 < a.nblk) ? pr[b + 16] : 0.f;
-      s2 += (b + 32 < a.nblk) ? pr[b + 32] : 0.f;
-      s3 += (b + 48 < a.nblk) ? pr[b + 48] : 0.f;
+  const int l16 = tid & 15, groups = nthr >> 4;
+  for (int rs0 = tid >> 4; rs0 < rows_here; rs0 += 4 * groups) {
+    float sum[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int rs = rs0 + j * groups;
+      const float *pr = part + rs * a.ppitch;
+      float acc = 0.f;
+      if (rs < rows_here)
+      for (int b0 = l16; b0 < a.nblk; b0 += 64) {
+        float v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int b = b0 + 16 * t;
+          v[t] = pr[b < a.nblk ? b : a.nblk - 1];
+          v[t] = b < a.nblk ? v[t] : 0.f;
+        }
+        acc += (v[0] + v[1]) + (v[2] + v[3]);
+      }
+      sum[j] = acc;
     }
-    float sum = (s0 + s1) + (s2 + s3);
-    if (HAS_WEAK) {
-      for (int c = a.nblk + l16; c < a.kchunks; c += 16) {
-        const u32x4 wv = a.weak_w[row * a.kchunks + c];
-        const uint4 xv4 = xw_u[c];
-        sum = dot2(wv.x, xv4.x, sum);
-        sum = dot2(wv.y, xv4.y, sum);
-        sum = dot2(wv.z, xv4.z, sum);
-        sum = dot2(wv.w, xv4.w, sum);
+    if (HAS_WEAK && a.kchunks > a.nblk) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int rs = rs0 + j * groups;
+        const int row = rt0 * a.r + rs;
+        if (rs < rows_here)
+        for (int c = a.nblk + l16; c < a.kchunks; c += 16) {
+          const u32x4 wv = a.weak_w[row * a.kchunks + c];
+          const uint4 xv4 = xw_u[c];
+          sum[j] = dot2(wv.x, xv4.x, sum[j]);
+          sum[j] = dot2(wv.y, xv4.y, sum[j]);
+          sum[j] = dot2(wv.z, xv4.z, sum[j]);
+          sum[j] = dot2(wv.w, xv4.w, sum[j]);
+        }
       }
     }
-    sum = row16_sum(sum);
-    if (l16 == 0 && row < a.d_out) yn[row] = (_Float16)sum;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sum[j] = row16_sum(sum[j]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int rs = rs0 + j * groups, row = rt0 * a.r + rs;
+      if (l16 == 0 && rs < rows_here && row < a.d_out) yn[row] = (_Float16)sum[j];
+    }
   }
   TRACE(8);
 }
