@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
+CALIB_BYTES = 256 << 20
 
 WORKLOADS = {
     # name: (config index in the benchmark's list, layer indices, description, packed layout, default batch)
@@ -55,6 +56,8 @@ def main() -> int:
                     help="graph: the K timed steps are one HIP graph launch; eager: K*layers launches from Python")
     ap.add_argument("--footprint-gb", type=float, default=1.5, help="total bytes of packed copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calib", action="store_true",
+                    help="also run a few plain device copies of 256 MiB, for scaling rocprofv3's byte counters")
     ap.add_argument("--launch", default="", help="rtw,rsplit,waves,depth override for every layer (tuning)")
     args = ap.parse_args()
 
@@ -108,6 +111,14 @@ def main() -> int:
                 B.owq_linear(lin.handle, x.data_ptr(), y.data_ptr(), batch, raw)
 
     with torch.cuda.stream(stream):
+        if args.pmc_calib:
+            # a plain copy of known size: reads CALIB_BYTES and writes CALIB_BYTES per launch
+            src = torch.arange(CALIB_BYTES // 4, dtype=torch.int32, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                torch.add(src, 1, out=dst)            # an elementwise kernel of torch's own: copy with +1
+            stream.synchronize()
+            del src, dst
         run_steps(0, args.warmup)
         stream.synchronize()
         graph = None

@@ -80,10 +80,13 @@ typedef struct {
 
 /*
  * Two packed layouts hold the same content.  OWQ_LAYOUT_GEMV is built for single tokens
- * and small batches (one lane streams 128 columns of one row; batch rows are separate
- * passes over the weights).  OWQ_LAYOUT_TILE is built for batches (prefill): 32 rows by
- * 256 columns per tile, unpacked straight into matrix-core operands, 64 tokens per pass
- * over the weights.  Either layout accepts any batch; they differ in speed only.
+ * (one lane streams 128 columns of one row; a batch is one pass over the weights per token).
+ * OWQ_LAYOUT_TILE is built for batches: 32 rows by 256 columns per tile, unpacked straight
+ * into matrix-core operands, one pass over the weights per 64 tokens (half the matrix work
+ * for 32 tokens or fewer).  Either layout accepts any batch and gives the same result up to
+ * rounding; they differ in speed only.  The blob of the tile layout ends in a scratch area
+ * (staged activations, sums, fp32 partial results) that owq_linear uses at run time, so that
+ * the call needs neither an allocation nor a workspace argument.
  */
 #define OWQ_LAYOUT_GEMV 0
 #define OWQ_LAYOUT_TILE 1
@@ -99,7 +102,8 @@ typedef struct {
   int32_t d_out, d_in, bits, group_size, k;
   int32_t nblk, cw, r, nact, nslab, n_rt, d_out_pad, chunks, n_groups, kp;
   uint64_t off_codes, off_sz, off_weak_w, off_weak_idx, total_bytes;
-  /* tile layout only: block pairs per row, weak-column bit mask, run-time scratch area */
+  /* tile layout only: block pairs per row, weak-column bit mask, run-time scratch area;
+     scale/zero pairs are stored [group][row] in this layout, [row][group] in the other */
   int32_t layout, nbp;
   uint64_t off_wmask, off_scratch;
   /* launch shape (filled for handles only) */
@@ -169,11 +173,15 @@ owq_status_t owq_layer_info(owq_handle_t h, owq_layer_info_t *info);
 owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes);
 
 /*
- * Tuning hook for benchmarks: override the launch shape of the batch <= 16 path.
- * row_tiles_per_wg >= 1; row_splits divides row_tiles_per_wg; waves_per_wg in
- * [1, 8] divides nslab * row_splits; prefetch_depth in {2, 4, 8} (8 only with at most 4 waves).  A value of 0
- * keeps the current setting.  Rejected shapes leave the handle unchanged.
- * Not thread-safe against concurrent owq_linear on the same handle.
+ * Tuning hook for benchmarks: override the launch shape.  A value of 0 keeps the current
+ * setting; rejected shapes leave the handle unchanged.  Not thread-safe against concurrent
+ * owq_linear on the same handle.
+ *   GEMV layout: row_tiles_per_wg >= 1; row_splits divides row_tiles_per_wg; waves_per_wg in
+ *     [1, 8] divides nslab * row_splits; prefetch_depth in {2, 4, 8} (8 only with at most 4
+ *     waves).
+ *   Tile layout: row_tiles_per_wg = number of workgroups of the matrix kernel (at most what
+ *     the partial-result slots of the scratch area allow, see owq_layer_info_t.workgroups after
+ *     packing); waves_per_wg = 4 or 8; row_splits and prefetch_depth must be 0.
  */
 owq_status_t owq_set_launch(owq_handle_t h, int32_t row_tiles_per_wg, int32_t row_splits,
                             int32_t waves_per_wg, int32_t prefetch_depth);
