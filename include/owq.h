@@ -179,9 +179,12 @@ owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes);
  *   GEMV layout: row_tiles_per_wg >= 1; row_splits divides row_tiles_per_wg; waves_per_wg in
  *     [1, 8] divides nslab * row_splits; prefetch_depth in {2, 4, 8} (8 only with at most 4
  *     waves).
- *   Tile layout: row_tiles_per_wg = number of workgroups of the matrix kernel (at most what
- *     the partial-result slots of the scratch area allow, see owq_layer_info_t.workgroups after
- *     packing); waves_per_wg = 4 or 8; row_splits and prefetch_depth must be 0.
+ *   Tile layout: waves_per_wg = 4 or 8; prefetch_depth must be 0.  row_splits = S > 0: every
+ *     group of 64 * waves_per_wg rows is cut into S column ranges, one workgroup each
+ *     (S <= d_in / 256; row_tiles_per_wg must be 0 or that number of workgroups).
+ *     row_splits = 0 and row_tiles_per_wg = P > 0: the flattened (row group, 256-column step)
+ *     sequence is cut into P equal ranges.  Both 0: the default for the chosen waves_per_wg.
+ *     The number of workgroups is limited by the partial-result slots of the scratch area.
  */
 owq_status_t owq_set_launch(owq_handle_t h, int32_t row_tiles_per_wg, int32_t row_splits,
                             int32_t waves_per_wg, int32_t prefetch_depth);

@@ -87,13 +87,11 @@ static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_ha
   int32_t lds_limit = 0;
   if (device_lds_limit(&lds_limit) != 0) return OWQ_ERR_HIP;
   LaunchShape shape{};
-  int32_t tile_grid = 0, tile_waves = 4;
+  int32_t tile_grid = 0, tile_waves = 4, tile_split = 0;
   if (g.layout == OWQ_LAYOUT_TILE) {
     if (lds_limit < 65536) return OWQ_ERR_UNSUPPORTED;
-    tile_grid = tile_grid_limit(g, tile_waves);
+    tile_default_shape(g, tile_waves, &tile_grid, &tile_split);
     if (tile_grid < 1) return OWQ_ERR_UNSUPPORTED;
-    // grouped layers keep more state per wave: one workgroup per compute unit at a time
-    if (g.n_groups > 1 && tile_grid > kTileGridMax / 2) tile_grid = kTileGridMax / 2;
     const int e = prepare_tile_kernels(g, lds_limit);
     if (e == (int)hipErrorInvalidValue) return OWQ_ERR_UNSUPPORTED;
     if (e != 0) return OWQ_ERR_HIP;
@@ -109,6 +107,7 @@ static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_ha
   h->shape = shape;
   h->tile_grid = tile_grid;
   h->tile_waves = tile_waves;
+  h->tile_split = tile_split;
   h->dev_buf = dev_buf;
   h->lds_limit = lds_limit;
   const uint8_t *base = static_cast<const uint8_t *>(dev_buf);
@@ -163,7 +162,7 @@ owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, v
   if (!x || !y) return OWQ_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(x) % 2 != 0 || reinterpret_cast<uintptr_t>(y) % 2 != 0) return OWQ_ERR_BUFFER;
   const int herr = h->info.layout == OWQ_LAYOUT_TILE
-                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_waves, x, y, batch, stream)
+                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_split, h->tile_waves, x, y, batch, stream)
                        : launch_gemv(h->info, h->shape, h->dev, x, y, batch, stream);
   if (herr != 0) {
     h->info.last_hip_error = herr;
@@ -184,7 +183,7 @@ owq_status_t owq_layer_info(owq_handle_t h, owq_layer_info_t *info) {
   if (!info) return OWQ_ERR_NULL;
   *info = h->info;
   info->row_tiles_per_wg = h->shape.rtw;
-  info->row_splits = h->shape.rsplit;
+  info->row_splits = h->info.layout == OWQ_LAYOUT_TILE ? h->tile_split : h->shape.rsplit;
   info->waves_per_wg = h->info.layout == OWQ_LAYOUT_TILE ? h->tile_waves : h->shape.waves;
   info->prefetch_depth = h->shape.depth;
   info->workgroups = h->info.layout == OWQ_LAYOUT_TILE ? h->tile_grid : h->shape.nwg;
@@ -207,16 +206,29 @@ owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes) {
 owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t waves, int32_t depth) {
   if (!live(h)) return OWQ_ERR_HANDLE;
   if (h->info.layout == OWQ_LAYOUT_TILE) {
-    // tile layout: workgroups of the main kernel and its waves per workgroup (4 or 8)
-    if (rsplit || depth) return OWQ_ERR_SHAPE;
+    // tile layout: workgroups of the main kernel, column ranges per row group, waves per workgroup
+    if (depth) return OWQ_ERR_SHAPE;
     const int32_t wv = waves ? waves : h->tile_waves;
     if (wv != 4 && wv != 8) return OWQ_ERR_SHAPE;
     const int32_t lim = tile_grid_limit(h->info, wv);
     if (lim < 1) return OWQ_ERR_UNSUPPORTED;
-    int32_t gr = rtw ? rtw : h->tile_grid;
-    if (rtw < 0 || (rtw && rtw > lim)) return OWQ_ERR_SHAPE;
-    if (gr > lim) gr = lim;
+    int32_t gr = 0, sp = 0;
+    if (rsplit > 0) {                       // aligned ranges: grid follows from the split
+      const int32_t n_rg = (h->info.n_rt + 2 * wv - 1) / (2 * wv);
+      if (rsplit > h->info.nbp || (int64_t)n_rg * rsplit > lim) return OWQ_ERR_SHAPE;
+      if (rtw && rtw != n_rg * rsplit) return OWQ_ERR_SHAPE;
+      gr = n_rg * rsplit;
+      sp = rsplit;
+    } else if (rsplit < 0) {
+      return OWQ_ERR_SHAPE;
+    } else if (rtw) {                       // equal ranges of the whole sequence
+      if (rtw < 0 || rtw > lim) return OWQ_ERR_SHAPE;
+      gr = rtw;
+    } else {
+      tile_default_shape(h->info, wv, &gr, &sp);
+    }
     h->tile_grid = gr;
+    h->tile_split = sp;
     h->tile_waves = wv;
     return OWQ_OK;
   }

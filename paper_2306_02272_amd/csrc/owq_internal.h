@@ -72,8 +72,11 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 // Tile path (defined in owq_tile.hip): three launches per pass of up to 64 tokens.
 // blob = DEVICE address of the packed blob; grid = workgroups of the main kernel.
 // waves = waves per workgroup of the main kernel (4 or 8).
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t waves, const void *x, void *y,
-                int32_t batch, void *stream);
+// split > 0: grid = row groups x split, every row group cut into `split` column ranges;
+// split = 0: the flattened (row group, column step) sequence cut into `grid` equal ranges.
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, const void *x,
+                void *y, int32_t batch, void *stream);
+void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split);
 int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves);
 int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit);   // LDS opt-in for grouped layers
 int device_lds_limit(int32_t *bytes);
@@ -89,4 +92,5 @@ struct owq_layer_s {
   int32_t lds_limit;
   int32_t tile_grid;     // workgroups of the tile kernel (tile layout only)
   int32_t tile_waves;    // its waves per workgroup: 4 or 8
+  int32_t tile_split;    // column ranges per row group, 0 = equal ranges of the whole sequence
 };

@@ -162,6 +162,8 @@ struct TileArgs {
   f4_t *slots;
   int nbp, n_rt, n_groups, bpg, nblk, d_out_pad;
   int steps;             // row groups x column steps
+  int split;             // > 0: every row group is cut into `split` ranges (grid = row groups x split);
+                         // 0: the whole flattened sequence is cut into gridDim.x equal ranges
 };
 
 // A operand of k-step S (16 columns) from the lane's dwords: four packed pairs 2^(10-o)+q.
@@ -255,7 +257,15 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
   extern __shared__ u32x4 lds[];                // two buffers
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int P = gridDim.x, p = blockIdx.x;
-  const int lo = (int)((long long)p * a.steps / P), hi = (int)((long long)(p + 1) * a.steps / P);
+  int lo, hi;
+  if (a.split > 0) {         // ranges aligned to row groups: workgroups of one range move in step
+    const int g0 = p / a.split, sp = p - g0 * a.split;
+    lo = g0 * a.nbp + (int)((long long)sp * a.nbp / a.split);
+    hi = g0 * a.nbp + (int)((long long)(sp + 1) * a.nbp / a.split);
+  } else {
+    lo = (int)((long long)p * a.steps / P);
+    hi = (int)((long long)(p + 1) * a.steps / P);
+  }
   if (lo >= hi) return;
   int rg = lo / a.nbp, bp = lo - rg * a.nbp;    // the step being computed
   int st = lo;
@@ -477,6 +487,7 @@ struct FinishArgs {
   const u32x4 *xw;       // [64][kp/8] units
   _Float16 *y;           // [ntok][d_out] of this pass
   int nbp, d_out, d_out_pad, ntok, steps, grid, kp;
+  int split;             // as in the main kernel
   int waves;             // waves per workgroup of the main kernel: a slot holds waves*64 rows
   int scaled;            // the partial results are already scaled (grouped layers)
 };
@@ -524,7 +535,14 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
   }
   // owners of the first and the last step of this row group
   const long long st0 = (long long)rg * a.nbp, st1 = st0 + a.nbp - 1;
-  const int p_first = (int)(((st0 + 1) * a.grid - 1) / a.steps), p_last = (int)(((st1 + 1) * a.grid - 1) / a.steps);
+  int p_first, p_last;
+  if (a.split > 0) {
+    p_first = rg * a.split;
+    p_last = p_first + a.split - 1;
+  } else {
+    p_first = (int)(((st0 + 1) * a.grid - 1) / a.steps);
+    p_last = (int)(((st1 + 1) * a.grid - 1) / a.steps);
+  }
   f2_t t = {0.f, 0.f};
   if (!a.scaled) t = a.tsum[n];
   f4_t sum[4];
@@ -633,8 +651,32 @@ int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves) {
   return lim < 0 ? 0 : (int32_t)lim;
 }
 
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t waves, const void *x, void *y,
-                int32_t batch, void *stream) {
+// Default work split: ranges aligned to row groups (fewer partial results, and the workgroups
+// of a range use the same activation tile at the same time, which keeps it in L2) unless that
+// costs more than a tenth in steps per workgroup against equal ranges of the whole sequence.
+void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split) {
+  const int32_t limit = tile_grid_limit(g, waves);
+  int32_t cap = waves == 8 ? kTileGridMax / 2 : kTileGridMax;
+  if (g.n_groups > 1 && waves == 4) cap = kTileGridMax / 2;   // grouped layers: one workgroup per compute unit
+  if (cap > limit) cap = limit;
+  const int64_t n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
+  const int64_t steps = n_rg * g.nbp;
+  *grid = cap;
+  *split = 0;
+  if (cap < 1) return;
+  int64_t sa = cap / n_rg;
+  if (sa > g.nbp) sa = g.nbp;
+  if (sa >= 1) {
+    const int64_t aligned = (g.nbp + sa - 1) / sa, equal = (steps + cap - 1) / cap;
+    if (aligned * 10 <= equal * 11) {
+      *grid = (int32_t)(n_rg * sa);
+      *split = (int32_t)sa;
+    }
+  }
+}
+
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, const void *x,
+                void *y, int32_t batch, void *stream) {
   const TileScratch ts = tile_scratch(g);
   uint8_t *base = static_cast<uint8_t *>(blob);
   uint8_t *scr = base + g.off_scratch;
@@ -643,6 +685,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t wav
   if (waves != 4 && waves != 8) return (int)hipErrorInvalidValue;
   if (grid < 1 || grid > tile_grid_limit(g, waves)) return (int)hipErrorInvalidValue;
   const int n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
+  if (split < 0 || split > g.nbp || (split > 0 && grid != n_rg * split)) return (int)hipErrorInvalidValue;
 
   StageArgs sa;
   sa.wmask = base + g.off_wmask;
@@ -662,6 +705,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t wav
   ta.nbp = g.nbp; ta.n_rt = g.n_rt; ta.n_groups = g.n_groups; ta.nblk = g.nblk; ta.d_out_pad = g.d_out_pad;
   ta.bpg = g.group_size ? g.group_size / kBlockCols : g.nblk;
   ta.steps = n_rg * g.nbp;
+  ta.split = split;
 
   FinishArgs fa;
   fa.slots = ta.slots;
@@ -670,7 +714,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t wav
   fa.weak_w = reinterpret_cast<const u32x4 *>(base + g.off_weak_w);
   fa.xw = reinterpret_cast<const u32x4 *>(sa.xw);
   fa.nbp = g.nbp; fa.d_out = g.d_out; fa.d_out_pad = g.d_out_pad;
-  fa.steps = ta.steps; fa.grid = grid; fa.kp = g.kp; fa.waves = waves;
+  fa.steps = ta.steps; fa.grid = grid; fa.kp = g.kp; fa.waves = waves; fa.split = split;
   fa.scaled = grouped ? 1 : 0;
 
   const _Float16 *xp = static_cast<const _Float16 *>(x);

@@ -91,6 +91,26 @@ def test_any_number_of_workgroups_gives_the_same_sums(env, grid):
     check(run_gpu(env, layer, x, grid), owq_ref.owq_linear_layer(layer, x), f"grid {grid}")
 
 
+@pytest.mark.parametrize("split,waves", [(1, 4), (2, 4), (3, 4), (4, 4), (2, 8), (3, 8)])
+def test_column_ranges_aligned_to_row_groups(env, split, waves):
+    # 4 column steps per row group cut into `split` ranges; 3 row groups of 256 rows or 2 of 512
+    torch, B = env
+    layer = make_layer(LayerSpec("split", 1024, 700, 4, 0, 16, 32))
+    x = make_x(layer, 64)
+    lin = B.OwqLinear(layer, layout=TILE)
+    B.owq_set_launch(lin.handle, 0, split, waves, 0)
+    info = lin.info()
+    print(f"split {split} waves {waves}: {info.workgroups} workgroups", flush=True)
+    assert info.row_splits == split and info.waves_per_wg == waves
+    assert info.workgroups == split * (3 if waves == 4 else 2)
+    y = lin(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    check(y.cpu().numpy(), owq_ref.owq_linear_layer(layer, x), f"split {split} waves {waves}")
+    with pytest.raises(B.OwqError):
+        B.owq_set_launch(lin.handle, 0, 5, waves, 0)       # more ranges than column steps
+    lin.close()
+
+
 def test_all_columns_weak_reproduces_fp16_matmul(env):
     rng = np.random.default_rng(3)
     d_out, d_in = 48, 384
