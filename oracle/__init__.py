@@ -12,6 +12,10 @@ Pins (see tests marked "not gpu"):
                    hand-enumerated tiny layers; moving a column from the dense
                    to the weak set when its dequantised value is exact in fp16;
                    the pure-Python triple loop in `owq_linear_loops`.
+  owq_linear_multi_ref
+                   all tokens on one task against owq_linear_ref; the difference between two
+                   task assignments against a plain matrix product with the difference of
+                   the weak columns; nested Python loops on a tiny layer.
   pack / unpack    bit-exact round trip, byte count, a bit-by-bit scalar
                    address function written separately from the vectorised
                    packer, walking-ones patterns.

@@ -112,3 +112,31 @@ def parity_errors(y_test, y_ref64):
     rms = np.sqrt(np.mean(b * b))
     mx = np.max(np.abs(a - b)) / rms if rms > 0 else float(np.max(np.abs(a - b)))
     return float(rel), float(mx)
+
+
+def owq_linear_multi_ref(codes, scale, zero, group_size, weak_idx, weak_sets, task_id, x,
+                         row_chunk: int = 1024) -> np.ndarray:
+    """Several tasks sharing one dense low-bit matrix (paper, section "Weak Column Tuning":
+    only the weak columns are tuned per task, the dense matrix and the indices are shared).
+
+        Y[n, i] = sum_{j not in S} s[i, g(j)] (q[i, j] - z[i, g(j)]) x[n, j]
+                + sum_{t < k} Ww[task_id[n]][i, t] x[n, idx[t]]
+
+    weak_sets: sequence of [d_out, k] fp16 arrays, task_id: [batch] ints in [0, len(weak_sets)).
+    Written token by token, each with its own weak columns; no sharing of work between tokens.
+    """
+    codes = np.asarray(codes)
+    d_out, d_in = codes.shape
+    x64 = np.asarray(x, dtype=np.float64)
+    idx = np.asarray(weak_idx, dtype=np.int64)
+    task_id = [int(t) for t in task_id]
+    assert len(task_id) == x64.shape[0] and all(0 <= t < len(weak_sets) for t in task_id)
+    y = np.empty((x64.shape[0], d_out), dtype=np.float64)
+    for r0 in range(0, d_out, row_chunk):
+        r1 = min(d_out, r0 + row_chunk)
+        dense = dequantize_dense(codes[r0:r1], np.asarray(scale)[r0:r1], np.asarray(zero)[r0:r1],
+                                 group_size, idx)
+        for n in range(x64.shape[0]):
+            ww = np.asarray(weak_sets[task_id[n]], dtype=np.float64)[r0:r1]
+            y[n, r0:r1] = dense @ x64[n] + ww @ x64[n, idx]
+    return y

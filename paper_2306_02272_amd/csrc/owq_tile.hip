@@ -286,17 +286,23 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
       if (++c_bp == a.nbp) { c_bp = 0; ++c_rg; }
     }
   };
-  u32x4 xg[XU];
-  u32x4 auxg = {0u, 0u, 0u, 0u};
+  // Staging registers.  8 waves (4 or fewer units per thread): three sets rotating with the code
+  // buffers, the tile of step st + 2 is fetched during step st and goes to LDS at the end of
+  // step st + 1, when it has long arrived.  4 waves: one set, one step ahead.
+  constexpr int XSETS = WAVES == 8 ? 3 : 1;
+  u32x4 xg[XSETS][XU];
+  u32x4 auxg[XSETS];
+#pragma unroll
+  for (int i = 0; i < XSETS; ++i) auxg[i] = (u32x4){0u, 0u, 0u, 0u};
   int x_st = lo, x_bp = bp, x_rg = rg;
   auto unit_of = [&](int j) {
     const int i = tid + THREADS * j;
     return NT == 2 ? i : ((i >> 6) * 128 + (i & 63));
   };
-  auto fetch_x = [&](int j) { xg[j] = a.xs[(size_t)x_bp * kUnitsPerTile + unit_of(j)]; };
+  auto fetch_x = [&](int set, int j) { xg[set][j] = a.xs[(size_t)x_bp * kUnitsPerTile + unit_of(j)]; };
   // grouped layers: thread t < ROWS/2 stages (scale, zero) of 4 rows of one block of the step,
   // the next 64 threads stage the sums of 2 tokens of one block
-  auto fetch_aux = [&]() {
+  auto fetch_aux = [&](int set) {
     if constexpr (GROUPED) {
       const u32x4 *src = reinterpret_cast<const u32x4 *>(a.sz);
       if (tid < ROWS / 2) {
@@ -310,7 +316,7 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
         const int u = tid - ROWS / 2;
         src = reinterpret_cast<const u32x4 *>(a.bsum + (size_t)(2 * x_bp + (u >> 5)) * 64 + (u & 31) * 2);
       }
-      auxg = *src;
+      auxg[set] = *src;
     }
   };
   auto advance_x = [&]() {
@@ -319,26 +325,26 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
       if (++x_bp == a.nbp) { x_bp = 0; ++x_rg; }
     }
   };
-  auto store_x = [&](int buf) {
+  auto store_x = [&](int set, int buf) {
 #pragma unroll
-    for (int j = 0; j < XU; ++j) lds[buf * BUF_UNITS + unit_of(j)] = xg[j];
+    for (int j = 0; j < XU; ++j) lds[buf * BUF_UNITS + unit_of(j)] = xg[set][j];
     if constexpr (GROUPED) {
       if (tid < ROWS / 2) {
-        const u32 d[4] = {auxg.x, auxg.y, auxg.z, auxg.w};
+        const u32 d[4] = {auxg[set].x, auxg[set].y, auxg[set].z, auxg[set].w};
         f4_t lo4 = {half_lo(d[0]), half_hi(d[0]), half_lo(d[1]), half_hi(d[1])};
         f4_t hi4 = {half_lo(d[2]), half_hi(d[2]), half_lo(d[3]), half_hi(d[3])};
         f4_t *dst = reinterpret_cast<f4_t *>(lds + buf * BUF_UNITS + kUnitsPerTile) + tid * 2;
         dst[0] = lo4;
         dst[1] = hi4;
       } else if (tid < ROWS / 2 + 64) {
-        lds[buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS + (tid - ROWS / 2)] = auxg;
+        lds[buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS + (tid - ROWS / 2)] = auxg[set];
       }
     }
   };
 
 #pragma unroll
-  for (int j = 0; j < XU; ++j) fetch_x(j);
-  fetch_aux();
+  for (int j = 0; j < XU; ++j) fetch_x(0, j);
+  fetch_aux(0);
   advance_x();
 #pragma unroll
   for (int sl = 0; sl < 2; ++sl) {
@@ -373,8 +379,14 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
       __syncthreads();
     }
   }
-  store_x(0);
+  store_x(0, 0);
   __syncthreads();
+  if constexpr (XSETS == 3) {      // the tile of the second step
+#pragma unroll
+    for (int j = 0; j < XU; ++j) fetch_x(1, j);
+    fetch_aux(1);
+    advance_x();
+  }
 
   Magic M;
   M.init();
@@ -444,10 +456,11 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
     }
     auto between = [&](auto ks) __attribute__((always_inline)) {
       constexpr int S = decltype(kstep_index(ks))::value;
-      if constexpr (S < XU) fetch_x(S);                       // activations of step st + 1
+      constexpr int XF = XSETS == 3 ? (J + 2) % 3 : 0;         // set being fetched: step st + 2 or st + 1
+      if constexpr (S < XU) fetch_x(XF, S);
       if constexpr (S >= 8 && S < 8 + 2 * CH) fetch_code((J + 2) % 3, (S - 8) / CH, (S - 8) % CH);   // codes of step st + 2
       if constexpr (S == 8 + 2 * CH - 1) advance_codes();
-      if constexpr (S == XU - 1) { fetch_aux(); advance_x(); }
+      if constexpr (S == XU - 1) { fetch_aux(XF); advance_x(); }
       if constexpr (GROUPED && (S == 7 || S == 15)) block_epilogue(S >> 3, par);
     };
     KSteps<BITS, NT, 0>::run(wd0, wd1, lds + par * BUF_UNITS, lane, M, acc, between);
@@ -462,7 +475,7 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
       }
     }
     if (last_of_group) { bp = 0; ++rg; } else { ++bp; }
-    store_x(par ^ 1);
+    store_x(XSETS == 3 ? (J + 1) % 3 : 0, par ^ 1);
     __syncthreads();
     par ^= 1;
     ++st;

@@ -144,3 +144,47 @@ def test_fp16_rounding_and_error_measures():
     rel, mx = owq_ref.parity_errors(np.array([3.0, 4.0 + 0.5]), np.array([3.0, 4.0]))
     assert rel == pytest.approx(0.5 / 5.0)
     assert mx == pytest.approx(0.5 / math.sqrt(12.5))
+
+
+# ---- several tasks sharing the dense matrix (section "Weak Column Tuning") ------------------
+
+def _multi_case(seed=21, d_in=256, d_out=24, k=6, n_sets=3, batch=7):
+    rng = np.random.default_rng(seed)
+    L = make_layer(LayerSpec("multi", d_in, d_out, 3, 128, k, seed))
+    sets = [rng.normal(0, 0.02, size=(d_out, k)).astype(np.float16) for _ in range(n_sets)]
+    task = rng.integers(0, n_sets, size=batch)
+    x = make_x(L, batch)
+    return L, sets, task, x
+
+
+def test_multi_task_with_one_task_is_the_single_task_layer():
+    L, sets, task, x = _multi_case()
+    for t in range(len(sets)):
+        want = owq_ref.owq_linear_ref(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, sets[t], x)
+        got = owq_ref.owq_linear_multi_ref(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, sets,
+                                           [t] * x.shape[0], x)
+        np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-13)
+
+
+def test_multi_task_difference_is_the_difference_of_the_weak_columns():
+    # moving token n from task a to task b changes y[n] by (Ww_b - Ww_a) x[n, idx] and nothing else
+    L, sets, task, x = _multi_case(seed=22)
+    base = owq_ref.owq_linear_multi_ref(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, sets, task, x)
+    task2 = task.copy()
+    n = 3
+    task2[n] = (task[n] + 1) % len(sets)
+    moved = owq_ref.owq_linear_multi_ref(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, sets, task2, x)
+    xw = x[n, L.weak_idx].astype(np.float64)
+    delta = (sets[task2[n]].astype(np.float64) - sets[task[n]].astype(np.float64)) @ xw
+    np.testing.assert_allclose(moved[n] - base[n], delta, rtol=0, atol=1e-12)
+    keep = np.arange(x.shape[0]) != n
+    np.testing.assert_array_equal(moved[keep], base[keep])
+
+
+def test_multi_task_tiny_layer_by_loops():
+    L, sets, task, x = _multi_case(seed=23, d_in=128, d_out=3, k=2, n_sets=2, batch=4)
+    got = owq_ref.owq_linear_multi_ref(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, sets, task, x)
+    for n in range(4):
+        want = owq_ref.owq_linear_loops(L.codes.tolist(), L.scale.tolist(), L.zero.tolist(), L.group_size,
+                                        L.weak_idx.tolist(), sets[task[n]].tolist(), [x[n].tolist()])
+        np.testing.assert_allclose(got[n], np.array(want[0]), rtol=1e-12, atol=1e-12)
