@@ -56,6 +56,8 @@ def main() -> int:
                     help="graph: the K timed steps are one HIP graph launch; eager: K*layers launches from Python")
     ap.add_argument("--footprint-gb", type=float, default=1.5, help="total bytes of packed copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tasks", type=int, default=0,
+                    help="N > 0: owq_linear_multi with N sets of weak columns and random task ids per token")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run a few plain device copies of 256 MiB, for scaling rocprofv3's byte counters")
     ap.add_argument("--launch", default="", help="rtw,rsplit,waves,depth override for every layer (tuning)")
@@ -98,6 +100,12 @@ def main() -> int:
         for st in sets:
             for lin in st:
                 B.owq_set_launch(lin.handle, rtw, rsplit, waves, depth)
+    tables = None
+    if args.tasks > 0:
+        rng = np.random.default_rng(1)
+        tables = [[lin.add_weak_sets([rng.normal(0, 0.02, size=(L.d_out, L.k)).astype(np.float16)
+                                      for _ in range(args.tasks)]) for lin, L in zip(st, layers)] for st in sets]
+        task_ids = torch.from_numpy(rng.integers(0, args.tasks, size=batch).astype(np.int32)).cuda()
     xs = [torch.from_numpy(x).cuda() for x in xs_host]
     ys = [torch.empty((batch, s.d_out), dtype=torch.float16, device="cuda") for s in specs]
 
@@ -107,8 +115,13 @@ def main() -> int:
     def run_steps(first_step: int, n: int):
         for t in range(first_step, first_step + n):
             st = sets[t % copies]
-            for lin, x, y in zip(st, xs, ys):
-                B.owq_linear(lin.handle, x.data_ptr(), y.data_ptr(), batch, raw)
+            for i, (lin, x, y) in enumerate(zip(st, xs, ys)):
+                if tables is None:
+                    B.owq_linear(lin.handle, x.data_ptr(), y.data_ptr(), batch, raw)
+                else:
+                    tab = tables[t % copies][i][0]
+                    B.owq_linear_multi(lin.handle, tab.data_ptr(), args.tasks, task_ids.data_ptr(), x.data_ptr(),
+                                       y.data_ptr(), batch, raw)
 
     with torch.cuda.stream(stream):
         if args.pmc_calib:
@@ -191,7 +204,7 @@ def main() -> int:
         "dtype": "f16 activations x 3/4-bit codes, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": desc, "batch": batch, "layers": [s.name for s in specs],
-                   "packed_copies": copies, "launch_mode": args.mode,
+                   "packed_copies": copies, "launch_mode": args.mode, "tasks": args.tasks,
                    "bytes_per_step": step_bytes},
         "pct_of_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "us_per_call": round(wall_s / launches * 1e6, 3),

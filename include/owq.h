@@ -40,7 +40,7 @@ typedef enum {
   OWQ_ERR_BITS = 3,       /* bits is neither 3 nor 4 */
   OWQ_ERR_GROUP = 4,      /* group_size is neither 0 nor a positive multiple of 128 */
   OWQ_ERR_CODE_RANGE = 5, /* a code at a non-weak column is >= 2^bits */
-  OWQ_ERR_INDEX = 6,      /* k out of [0, d_in], or weak_idx not strictly ascending in [0, d_in) */
+  OWQ_ERR_INDEX = 6,      /* k out of [0, d_in], weak_idx not strictly ascending in [0, d_in), or n_sets out of range */
   OWQ_ERR_BUFFER = 7,     /* a buffer is too small or misaligned */
   OWQ_ERR_BATCH = 8,      /* batch < 0 or above OWQ_MAX_BATCH */
   OWQ_ERR_HANDLE = 9,     /* not a live handle */
@@ -50,6 +50,7 @@ typedef enum {
 } owq_status_t;
 
 #define OWQ_MAX_BATCH 65535
+#define OWQ_MAX_WEAK_SETS 65536
 #define OWQ_FORMAT_VERSION 1
 
 /*
@@ -162,6 +163,33 @@ owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t
  * its blob: calls on one such handle must not overlap in time.
  */
 owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream);
+
+/*
+ * Weak-column tuning (section "Weak Column Tuning" of the paper: after quantisation only the
+ * fp16 weak columns are trained, per task; the low-bit matrix and the weak indices are shared).
+ *
+ * owq_update_weak replaces the layer's own weak columns in place: weak_w HOST, fp16 bit
+ * patterns [d_out][k] row-major (may be NULL if k == 0).  The copy is enqueued on stream and
+ * the call returns after it has completed; no owq_linear on this handle may be in flight.
+ *
+ * owq_weak_set_bytes / owq_pack_weak_set make a further set of weak columns for the same layer
+ * (same k, same indices) in caller-owned DEVICE memory dev_buf (16-byte aligned, at least
+ * owq_weak_set_bytes bytes, kept alive and unmodified while calls use it).
+ *
+ * owq_linear_multi: as owq_linear, but token n takes its weak columns from
+ * weak_sets[task_id[n]] when 0 <= task_id[n] < n_sets, and the layer's own otherwise:
+ *     y[n, i] = dense part of x[n] + sum_t Ww[task_id[n]][i, t] * x[n, weak_idx[t]]
+ *   weak_sets  DEVICE array of n_sets DEVICE pointers, each written by owq_pack_weak_set for
+ *              this layer; 1 <= n_sets <= OWQ_MAX_WEAK_SETS; only entries that some token
+ *              selects are read
+ *   task_id    DEVICE int32 [batch]
+ * Same rounding, stream and overlap rules as owq_linear.
+ */
+owq_status_t owq_update_weak(owq_handle_t h, const uint16_t *weak_w, void *stream);
+owq_status_t owq_weak_set_bytes(owq_handle_t h, size_t *bytes);
+owq_status_t owq_pack_weak_set(owq_handle_t h, const uint16_t *weak_w, void *dev_buf, size_t dev_bytes, void *stream);
+owq_status_t owq_linear_multi(owq_handle_t h, const void *const *weak_sets, int32_t n_sets, const int32_t *task_id,
+                              const void *x, void *y, int32_t batch, void *stream);
 
 /* Release the handle (the host-side record only; dev_buf stays with the caller). */
 owq_status_t owq_free_layer(owq_handle_t h);

@@ -27,7 +27,7 @@ OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE = 0, 1
 # every symbol include/owq.h declares
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
            "owq_open_packed", "owq_linear", "owq_free_layer", "owq_layer_info", "owq_export_packed", "owq_set_launch",
-           "owq_status_str"]
+           "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_status_str"]
 
 
 class OwqError(RuntimeError):
@@ -83,6 +83,10 @@ def lib():
         L.owq_layer_info.argtypes = [P, C.POINTER(LayerInfo)]
         L.owq_export_packed.argtypes = [P, P, SZ]
         L.owq_set_launch.argtypes = [P, I32, I32, I32, I32]
+        L.owq_update_weak.argtypes = [P, P, P]
+        L.owq_weak_set_bytes.argtypes = [P, C.POINTER(SZ)]
+        L.owq_pack_weak_set.argtypes = [P, P, P, SZ, P]
+        L.owq_linear_multi.argtypes = [P, P, I32, P, P, P, I32, P]
         for n in EXPORTS:
             getattr(L, n).restype = C.c_int
         L.owq_status_str.argtypes = [C.c_int]
@@ -191,6 +195,39 @@ def owq_set_launch(handle: int, row_tiles_per_wg=0, row_splits=0, waves_per_wg=0
                                 prefetch_depth), "owq_set_launch")
 
 
+def _weak_host(weak_w):
+    a = np.ascontiguousarray(weak_w)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def owq_update_weak(handle: int, weak_w, stream: int = 0) -> None:
+    a = _weak_host(weak_w)
+    _check(lib().owq_update_weak(C.c_void_p(handle), a.ctypes.data if a.size else None, C.c_void_p(stream)),
+           "owq_update_weak")
+
+
+def owq_weak_set_bytes(handle: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().owq_weak_set_bytes(C.c_void_p(handle), C.byref(n)), "owq_weak_set_bytes")
+    return int(n.value)
+
+
+def owq_pack_weak_set(handle: int, weak_w, dev_ptr: int, dev_bytes: int, stream: int = 0) -> None:
+    a = _weak_host(weak_w)
+    _check(lib().owq_pack_weak_set(C.c_void_p(handle), a.ctypes.data if a.size else None, C.c_void_p(dev_ptr),
+                                   dev_bytes, C.c_void_p(stream)), "owq_pack_weak_set")
+
+
+def owq_linear_multi(handle: int, weak_sets_ptr: int, n_sets: int, task_id_ptr: int, x_ptr: int, y_ptr: int,
+                     batch: int, stream: int = 0) -> None:
+    _check(lib().owq_linear_multi(C.c_void_p(handle), C.c_void_p(weak_sets_ptr), n_sets, C.c_void_p(task_id_ptr),
+                                  C.c_void_p(x_ptr), C.c_void_p(y_ptr), batch, C.c_void_p(stream)),
+           "owq_linear_multi")
+
+
 def owq_status_str(status: int) -> str:
     return lib().owq_status_str(status).decode()
 
@@ -228,6 +265,30 @@ class OwqLinear:
             out = torch.empty((batch, self.d_out), dtype=torch.float16, device=x.device)
         owq_linear(self.handle, x.data_ptr(), out.data_ptr(), batch,
                    torch.cuda.current_stream().cuda_stream)
+        return out
+
+    def add_weak_sets(self, sets):
+        """Upload further sets of weak columns ([d_out, k] fp16 each); returns (pointer table, buffers)."""
+        torch = self.torch
+        nbytes = max(16, owq_weak_set_bytes(self.handle))
+        bufs = []
+        for wset in sets:
+            b = torch.empty(nbytes, dtype=torch.uint8, device=self.buf.device)
+            owq_pack_weak_set(self.handle, wset, b.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
+            bufs.append(b)
+        table = torch.tensor([b.data_ptr() for b in bufs], dtype=torch.int64, device=self.buf.device)
+        return table, bufs
+
+    def multi(self, x, table, task_id, out=None):
+        """owq_linear_multi: task_id an int32 CUDA tensor [batch], table from add_weak_sets."""
+        torch = self.torch
+        assert x.dtype == torch.float16 and x.is_cuda and x.is_contiguous() and x.shape[-1] == self.d_in
+        batch = x.numel() // self.d_in
+        assert task_id.dtype == torch.int32 and task_id.is_cuda and task_id.numel() == batch
+        if out is None:
+            out = torch.empty((batch, self.d_out), dtype=torch.float16, device=x.device)
+        owq_linear_multi(self.handle, table.data_ptr(), int(table.numel()), task_id.data_ptr(), x.data_ptr(),
+                         out.data_ptr(), batch, torch.cuda.current_stream().cuda_stream)
         return out
 
     def close(self):

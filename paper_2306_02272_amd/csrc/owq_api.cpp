@@ -155,20 +155,77 @@ owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t
   return make_handle(g, dev_buf, out);
 }
 
-owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream) {
-  if (!live(h)) return OWQ_ERR_HANDLE;
+static owq_status_t run_linear(owq_handle_t h, const TaskSets &tasks, const void *x, void *y, int32_t batch,
+                               void *stream) {
   if (batch < 0 || batch > OWQ_MAX_BATCH) return OWQ_ERR_BATCH;
   if (batch == 0) return OWQ_OK;
   if (!x || !y) return OWQ_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(x) % 2 != 0 || reinterpret_cast<uintptr_t>(y) % 2 != 0) return OWQ_ERR_BUFFER;
   const int herr = h->info.layout == OWQ_LAYOUT_TILE
-                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_split, h->tile_waves, x, y, batch, stream)
-                       : launch_gemv(h->info, h->shape, h->dev, x, y, batch, stream);
+                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_split, h->tile_waves, tasks, x, y, batch, stream)
+                       : launch_gemv(h->info, h->shape, h->dev, tasks, x, y, batch, stream);
   if (herr != 0) {
     h->info.last_hip_error = herr;
     return OWQ_ERR_HIP;
   }
   return OWQ_OK;
+}
+
+owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  const TaskSets one{nullptr, nullptr, 0};
+  return run_linear(h, one, x, y, batch, stream);
+}
+
+owq_status_t owq_linear_multi(owq_handle_t h, const void *const *weak_sets, int32_t n_sets, const int32_t *task_id,
+                              const void *x, void *y, int32_t batch, void *stream) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (!weak_sets || !task_id) return OWQ_ERR_NULL;
+  if (n_sets < 1 || n_sets > OWQ_MAX_WEAK_SETS) return OWQ_ERR_INDEX;
+  if (reinterpret_cast<uintptr_t>(weak_sets) % 8 != 0 || reinterpret_cast<uintptr_t>(task_id) % 4 != 0)
+    return OWQ_ERR_BUFFER;
+  const TaskSets tasks{weak_sets, task_id, n_sets};
+  return run_linear(h, tasks, x, y, batch, stream);
+}
+
+owq_status_t owq_weak_set_bytes(owq_handle_t h, size_t *bytes) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (!bytes) return OWQ_ERR_NULL;
+  const size_t n = (size_t)h->info.d_out_pad * h->info.kp * 2;
+  *bytes = (n + kAlign - 1) / kAlign * kAlign;
+  return OWQ_OK;
+}
+
+// weak_w (HOST, [d_out][k]) -> section layout -> DEVICE dst; waits for the copy
+static owq_status_t upload_weak(owq_handle_t h, const uint16_t *weak_w, void *dst, void *stream) {
+  const size_t n = (size_t)h->info.d_out_pad * h->info.kp * 2;
+  if (n == 0) return OWQ_OK;
+  uint16_t *host = nullptr;
+  if (hipHostMalloc(reinterpret_cast<void **>(&host), n, hipHostMallocDefault) != hipSuccess) return OWQ_ERR_HIP;
+  pack_weak_section(h->info, weak_w, host);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(dst, host, n, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipHostFree(host);
+  if (e != hipSuccess) {
+    h->info.last_hip_error = (int)e;
+    return OWQ_ERR_HIP;
+  }
+  return OWQ_OK;
+}
+
+owq_status_t owq_pack_weak_set(owq_handle_t h, const uint16_t *weak_w, void *dev_buf, size_t dev_bytes, void *stream) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (!dev_buf || (h->info.k > 0 && !weak_w)) return OWQ_ERR_NULL;
+  if (dev_bytes < (size_t)h->info.d_out_pad * h->info.kp * 2) return OWQ_ERR_BUFFER;
+  if (reinterpret_cast<uintptr_t>(dev_buf) % 16 != 0) return OWQ_ERR_BUFFER;
+  return upload_weak(h, weak_w, dev_buf, stream);
+}
+
+owq_status_t owq_update_weak(owq_handle_t h, const uint16_t *weak_w, void *stream) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (h->info.k > 0 && !weak_w) return OWQ_ERR_NULL;
+  return upload_weak(h, weak_w, static_cast<uint8_t *>(h->dev_buf) + h->info.off_weak_w, stream);
 }
 
 owq_status_t owq_free_layer(owq_handle_t h) {

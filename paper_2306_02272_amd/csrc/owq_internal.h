@@ -38,6 +38,9 @@ TileScratch tile_scratch(const owq_layer_info_t &g);
 // Full validation of a description (pointers, code range, index order).
 owq_status_t validate_desc(const owq_layer_desc_t *desc);
 
+// Weak-column section of a blob: [d_out_pad][kp] fp16, padding 0.  out has d_out_pad * kp entries.
+void pack_weak_section(const owq_layer_info_t &info, const uint16_t *weak_w, uint16_t *out);
+
 // Host packer: writes info->total_bytes bytes.
 void pack_blob(const owq_layer_desc_t *desc, const owq_layer_info_t &info, uint8_t *out);
 
@@ -65,7 +68,15 @@ LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit);
 struct DeviceLayer {
   const void *codes, *sz, *weak_w, *weak_idx;
 };
-int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev,
+// Several sets of weak columns for one dense matrix (all DEVICE memory): token n uses
+// weak_sets[task_id[n]] when that index is in [0, n_sets), else the layer's own columns.
+// task_id == nullptr: one task, the layer's own columns.
+struct TaskSets {
+  const void *const *weak_sets;
+  const int32_t *task_id;
+  int32_t n_sets;
+};
+int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev, const TaskSets &tasks,
                 const void *x, void *y, int32_t batch, void *stream);
 int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when needed
 
@@ -74,8 +85,8 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 // waves = waves per workgroup of the main kernel (4 or 8).
 // split > 0: grid = row groups x split, every row group cut into `split` column ranges;
 // split = 0: the flattened (row group, column step) sequence cut into `grid` equal ranges.
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, const void *x,
-                void *y, int32_t batch, void *stream);
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves,
+                const TaskSets &tasks, const void *x, void *y, int32_t batch, void *stream);
 void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split);
 int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves);
 int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit);   // LDS opt-in for grouped layers

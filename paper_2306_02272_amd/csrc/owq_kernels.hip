@@ -36,6 +36,11 @@ struct GemvArgs {
   _Float16 *y;
   int d_in, d_out, nblk, cw, nact, nslab, n_rt, r, n_groups, blocks_per_group;
   int k, kp, kchunks;
+  // several tasks (weak-column tuning): batch row n uses weak_sets[task_id[n]] if that index
+  // is in [0, n_sets), else the layer's own weak columns; task_id == nullptr: always its own
+  const void *const *weak_sets;
+  const int *task_id;
+  int n_sets;
   int xper;   // 16-byte activation units per thread (ceil)
   // host-made reciprocals: n / d == (n * magic) >> 16 for the small n that occur (checked on the host)
   u32 cw_magic, nslab_magic, rsplit_magic, bpg_magic;
@@ -192,7 +197,14 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   const u32 chunk_bytes = (u32)a.nact * 16u;
   const char *codes_b = reinterpret_cast<const char *>(a.codes);
   const char *sz_b = reinterpret_cast<const char *>(a.sz);
-  const char *wk_b = reinterpret_cast<const char *>(a.weak_w);
+  // A pointer read from memory is a generic one to the compiler; it is marked as pointing to
+  // global memory here so that the loads through it stay global loads with exact wait counts.
+  typedef const __attribute__((address_space(1))) char *gptr_t;
+  gptr_t wk_b = (gptr_t)reinterpret_cast<const char *>(a.weak_w);
+  if (HAS_WEAK && a.task_id != nullptr) {          // same for the whole workgroup
+    const int t = a.task_id[blockIdx.y];
+    if ((u32)t < (u32)a.n_sets) wk_b = (gptr_t)static_cast<const char *>(a.weak_sets[t]);
+  }
 
   // ---- (1) loads the set-up needs: activations and weak indices ------------------
   // Issued before the weight stream: loads complete in order, so waiting for
@@ -254,7 +266,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
       buf[d][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes_b + (oc + (u32)c * cs)));
     szb[d] = *reinterpret_cast<const u32 *>(sz_b + (live ? off_s : 0u));
     if (HAS_WEAK)
-      wkb[d] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wk_b + (live ? off_w : 0u)));
+      wkb[d] = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4 *)(wk_b + (live ? off_w : 0u)));
     off_c += str_c; off_s += str_s; off_w += str_w;
     ++fetched;
   };
@@ -405,7 +417,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
         const int row = rt0 * a.r + rs;
         if (rs < rows_here)
         for (int c = a.nblk + l16; c < a.kchunks; c += 16) {
-          const u32x4 wv = a.weak_w[row * a.kchunks + c];
+          const u32x4 wv = ((const __attribute__((address_space(1))) u32x4 *)wk_b)[row * a.kchunks + c];
           const uint4 xv4 = xw_u[c];
           sum[j] = dot2(wv.x, xv4.x, sum[j]);
           sum[j] = dot2(wv.y, xv4.y, sum[j]);
@@ -473,9 +485,10 @@ int device_lds_limit(int32_t *bytes) {
   return (int)hipSuccess;
 }
 
-int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev,
+int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev, const TaskSets &tasks,
                 const void *x, void *y, int32_t batch, void *stream) {
   GemvArgs a;
+  a.weak_sets = tasks.weak_sets; a.task_id = tasks.task_id; a.n_sets = tasks.n_sets;
   a.codes = static_cast<const u32x4 *>(dev.codes);
   a.sz = static_cast<const u32 *>(dev.sz);
   a.weak_w = static_cast<const u32x4 *>(dev.weak_w);

@@ -140,6 +140,12 @@ static void block_to_dwords(const uint8_t *q, int bits, uint32_t *dw) {
   }
 }
 
+void pack_weak_section(const owq_layer_info_t &g, const uint16_t *weak_w, uint16_t *out) {
+  std::memset(out, 0, (size_t)g.d_out_pad * g.kp * 2);
+  for (int64_t i = 0; i < g.d_out; ++i)
+    for (int32_t t = 0; t < g.k; ++t) out[i * g.kp + t] = weak_w[i * (int64_t)g.k + t];
+}
+
 void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *out) {
   std::memset(out, 0, g.total_bytes);
   std::vector<uint8_t> weak(d->d_in, 0);
@@ -204,9 +210,7 @@ void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *ou
       sz[dst] = (uint32_t)d->scale[src] | ((uint32_t)d->zero[src] << 16);
     }
 
-  uint16_t *ww = reinterpret_cast<uint16_t *>(out + g.off_weak_w);
-  for (int64_t i = 0; i < g.d_out; ++i)
-    for (int32_t t = 0; t < g.k; ++t) ww[i * g.kp + t] = d->weak_w[i * (int64_t)g.k + t];
+  if (g.k > 0) pack_weak_section(g, d->weak_w, reinterpret_cast<uint16_t *>(out + g.off_weak_w));
 
   int32_t *ix = reinterpret_cast<int32_t *>(out + g.off_weak_idx);
   for (int32_t t = 0; t < g.kp; ++t) ix[t] = t < g.k ? d->weak_idx[t] : -1;

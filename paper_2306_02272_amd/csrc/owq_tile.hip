@@ -502,6 +502,11 @@ struct FinishArgs {
   int nbp, d_out, d_out_pad, ntok, steps, grid, kp;
   int split;             // as in the main kernel
   int waves;             // waves per workgroup of the main kernel: a slot holds waves*64 rows
+  // several tasks: token n uses weak_sets[task_id[n]] if that index is in [0, n_sets), else
+  // the layer's own weak columns; task_id == nullptr: always its own
+  const void *const *weak_sets;
+  const int *task_id;    // of this pass
+  int n_sets;
   int scaled;            // the partial results are already scaled (grouped layers)
 };
 
@@ -528,22 +533,45 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
   if (kunits > 0) {
     int row = row_base + rtl * 32 + (lane & 31);
     if (row > a.d_out_pad - 1) row = a.d_out_pad - 1;
-    const u32x4 *wsrc = a.weak_w + (size_t)row * kunits, *xsrc = a.xw + (size_t)n * kunits;
+    const u32x4 *xsrc = a.xw + (size_t)n * kunits;
     const int kg = lane >> 5;
-    for (int s0 = 0; 2 * s0 < kunits; s0 += 4) {
-      u32x4 av[4], bv[4];
+    // the set of weak columns of this lane's token: -1 = the layer's own, -2 = no token
+    int mine = n < a.ntok ? -1 : -2;
+    if (a.task_id != nullptr && n < a.ntok) {
+      const int t = a.task_id[n];
+      if ((u32)t < (u32)a.n_sets) mine = t;
+    }
+    const int t_last = a.task_id != nullptr ? a.n_sets - 1 : -1;
+    typedef const __attribute__((address_space(1))) u32x4 *gptr_t;   // pointers read from memory: global
+    constexpr int KS = 8;                            // K-steps whose loads are in flight together
+    for (int s0 = 0; 2 * s0 < kunits; s0 += KS) {
+      // the gathered activations of these K-steps are the same for every set: fetched once
+      u32x4 bv[KS];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {      // four K-steps of loads in flight
+      for (int j = 0; j < KS; ++j) {
         const int u = 2 * (s0 + j) + kg;
-        const bool live = u < kunits;
-        const int uc = live ? u : 0;
-        av[j] = wsrc[uc];
-        bv[j] = xsrc[uc];
-        if (!live) av[j] = (u32x4){0u, 0u, 0u, 0u};
-        if (!live) bv[j] = (u32x4){0u, 0u, 0u, 0u};
+        bv[j] = xsrc[u < kunits ? u : 0];
+        if (u >= kunits) bv[j] = (u32x4){0u, 0u, 0u, 0u};
       }
+      for (int t = -1; t <= t_last; ++t) {           // one pass per set that some token of the tile uses
+        if (__ballot(mine == t) == 0ull) continue;
+        const gptr_t wbase = t < 0 ? (gptr_t)a.weak_w : (gptr_t)static_cast<const u32x4 *>(a.weak_sets[t]);
+        const gptr_t wsrc = wbase + (size_t)row * kunits;
+        const bool use = mine == t;
+        u32x4 av[KS];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) wk = mma(__builtin_bit_cast(h8_t, av[j]), __builtin_bit_cast(h8_t, bv[j]), wk);
+        for (int j = 0; j < KS; ++j) {
+          const int u = 2 * (s0 + j) + kg;
+          av[j] = wsrc[u < kunits ? u : 0];
+          if (u >= kunits) av[j] = (u32x4){0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+          if (2 * (s0 + j) >= kunits) continue;      // same for the whole wave
+          const u32x4 zero = {0u, 0u, 0u, 0u};
+          wk = mma(__builtin_bit_cast(h8_t, av[j]), __builtin_bit_cast(h8_t, use ? bv[j] : zero), wk);
+        }
+      }
     }
   }
   // owners of the first and the last step of this row group
@@ -688,8 +716,8 @@ void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid,
   }
 }
 
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, const void *x,
-                void *y, int32_t batch, void *stream) {
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves,
+                const TaskSets &tasks, const void *x, void *y, int32_t batch, void *stream) {
   const TileScratch ts = tile_scratch(g);
   uint8_t *base = static_cast<uint8_t *>(blob);
   uint8_t *scr = base + g.off_scratch;
@@ -729,6 +757,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t spl
   fa.nbp = g.nbp; fa.d_out = g.d_out; fa.d_out_pad = g.d_out_pad;
   fa.steps = ta.steps; fa.grid = grid; fa.kp = g.kp; fa.waves = waves; fa.split = split;
   fa.scaled = grouped ? 1 : 0;
+  fa.weak_sets = tasks.weak_sets; fa.n_sets = tasks.n_sets;
 
   const _Float16 *xp = static_cast<const _Float16 *>(x);
   _Float16 *yp = static_cast<_Float16 *>(y);
@@ -745,6 +774,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t spl
                        tile_lds_bytes(grouped, waves), st, ta);
     fa.y = yp + (size_t)t0 * g.d_out;
     fa.ntok = ntok;
+    fa.task_id = tasks.task_id ? tasks.task_id + t0 : nullptr;
     hipLaunchKernelGGL(owq_tile_finish, dim3((unsigned)(n_rg * waves), 1, 1), dim3(256, 1, 1), 0, st, fa);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
