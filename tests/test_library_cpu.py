@@ -136,3 +136,25 @@ def test_status_strings(lib):
     seen = {B.owq_status_str(s) for s in range(13)}
     assert len(seen) == 13 and "ok" in seen
     assert B.owq_status_str(99) == "unknown status"
+
+
+def test_layers_of_4_gib_or_more_are_refused(lib):
+    # the kernels address a blob with 32-bit byte offsets: shapes only, no data is touched
+    ok = B.make_desc(65536, 65536, 4, 0, 0)                   # 2 GiB of codes
+    assert B.owq_packed_bytes(ok) > 2 ** 31
+    big = B.make_desc(131072, 65536, 4, 0, 0)                 # 4 GiB of codes
+    assert _status(B.owq_packed_bytes, big) == B.OWQ_ERR_SHAPE
+    big3 = B.make_desc(200000, 65536, 3, 128, 0)
+    assert _status(B.owq_geometry, big3) == B.OWQ_ERR_SHAPE
+    tile = B.make_desc(131072, 65536, 4, 0, 0, layout=B.OWQ_LAYOUT_TILE)
+    assert _status(B.owq_packed_bytes, tile) == B.OWQ_ERR_SHAPE
+
+
+def test_dead_handles_are_refused_by_the_weak_column_calls(lib):
+    fake = (C.c_uint32 * 64)()
+    n = C.c_size_t(0)
+    assert B.lib().owq_weak_set_bytes(None, C.byref(n)) == B.OWQ_ERR_HANDLE
+    assert B.lib().owq_update_weak(C.addressof(fake), None, None) == B.OWQ_ERR_HANDLE
+    assert B.lib().owq_pack_weak_set(None, None, None, 0, None) == B.OWQ_ERR_HANDLE
+    assert B.lib().owq_linear_multi(C.addressof(fake), None, 1, None, None, None, 1, None) == B.OWQ_ERR_HANDLE
+    assert B.lib().owq_set_launch(None, 1, 1, 1, 2) == B.OWQ_ERR_HANDLE
