@@ -8,7 +8,11 @@ packed copies of the layers (distinct addresses, more than the 256 MB of
 last-level cache in total), as successive decoder blocks of a model would, so
 that the weights really come from HBM.
 
-Prints ONE JSON line; see the design doc for the meaning of each field.
+Prints ONE JSON line.  value = algorithmic bytes of a step / time of a step (GB/s);
+roofline.achieved = algorithmic bytes (or, on the tile layout, floating-point operations) per
+call / mean duration of a call from HIP events on the launch stream; roofline.traffic = HBM
+bytes per call from rocprofv3's FETCH_SIZE and WRITE_SIZE (profiles/traffic.json, written by
+bench_traffic.py); cpu_baseline = the CPU oracle timed on a bounded sample of the same step.
 """
 from __future__ import annotations
 
@@ -27,7 +31,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 CALIB_BYTES = 256 << 20
 
 WORKLOADS = {
-    # name: (config index in the benchmark's list, layer indices, description, packed layout, default batch)
+    # name: (index in the list of benchmark configurations, layer indices, description, packed layout, default batch)
     "opt6.7b-ffn": (2, [0, 1], "configs[2]: OPT-6.7B-like FFN pair, fc1 4096->16384 (k=32) + fc2 16384->4096 (k=128), 3-bit, group 128", 0, 1),
     "opt6.7b-attn": (1, [0], "configs[1]: OPT-6.7B-like attention projection 4096->4096, 3-bit per-channel, k=32", 0, 1),
     "target": (5, [0], "bandwidth-target layer 16384->4096, 3-bit per-channel, k=128", 0, 1),
