@@ -108,6 +108,7 @@ static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_ha
   h->tile_grid = tile_grid;
   h->tile_waves = tile_waves;
   h->tile_split = tile_split;
+  h->tile_small_split = 0;
   h->dev_buf = dev_buf;
   h->lds_limit = lds_limit;
   const uint8_t *base = static_cast<const uint8_t *>(dev_buf);
@@ -162,7 +163,7 @@ static owq_status_t run_linear(owq_handle_t h, const TaskSets &tasks, const void
   if (!x || !y) return OWQ_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(x) % 2 != 0 || reinterpret_cast<uintptr_t>(y) % 2 != 0) return OWQ_ERR_BUFFER;
   const int herr = h->info.layout == OWQ_LAYOUT_TILE
-                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_split, h->tile_waves, tasks, x, y, batch, stream)
+                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_split, h->tile_waves, h->tile_small_split, tasks, x, y, batch, stream)
                        : launch_gemv(h->info, h->shape, h->dev, tasks, x, y, batch, stream);
   if (herr != 0) {
     h->info.last_hip_error = herr;
@@ -264,7 +265,7 @@ owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t
   if (!live(h)) return OWQ_ERR_HANDLE;
   if (h->info.layout == OWQ_LAYOUT_TILE) {
     // tile layout: workgroups of the main kernel, column ranges per row group, waves per workgroup
-    if (depth) return OWQ_ERR_SHAPE;
+    if (depth < -1 || (depth > 0 && !tile_small_split_ok(h->info, depth))) return OWQ_ERR_SHAPE;
     const int32_t wv = waves ? waves : h->tile_waves;
     if (wv != 4 && wv != 8) return OWQ_ERR_SHAPE;
     const int32_t lim = tile_grid_limit(h->info, wv);
@@ -287,6 +288,7 @@ owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t
     h->tile_grid = gr;
     h->tile_split = sp;
     h->tile_waves = wv;
+    h->tile_small_split = depth;
     return OWQ_OK;
   }
   LaunchShape s = h->shape;

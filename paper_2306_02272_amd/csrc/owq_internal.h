@@ -85,8 +85,15 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 // waves = waves per workgroup of the main kernel (4 or 8).
 // split > 0: grid = row groups x split, every row group cut into `split` column ranges;
 // split = 0: the flattened (row group, column step) sequence cut into `grid` equal ranges.
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves,
+// small_split: column ranges per row tile of the one-launch kernel that takes passes of 32
+// tokens or fewer (0 = the library's choice, -1 = never use that kernel).
+int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, int32_t small_split,
                 const TaskSets &tasks, const void *x, void *y, int32_t batch, void *stream);
+// The one-launch kernel for 32 tokens or fewer (defined in owq_tile_small.hip).  Returns a
+// hipError_t as int, or -1 when the layer, the split or the alignment of x does not fit it.
+int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t split, const void *x, void *y, int32_t ntok,
+                      void *stream);
+bool tile_small_split_ok(const owq_layer_info_t &g, int32_t split);
 void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split);
 int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves);
 int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit);   // LDS opt-in for grouped layers
@@ -104,4 +111,5 @@ struct owq_layer_s {
   int32_t tile_grid;     // workgroups of the tile kernel (tile layout only)
   int32_t tile_waves;    // its waves per workgroup: 4 or 8
   int32_t tile_split;    // column ranges per row group, 0 = equal ranges of the whole sequence
+  int32_t tile_small_split;  // 32 tokens or fewer: column ranges per row tile, 0 = default, -1 = three-launch path
 };

@@ -29,11 +29,12 @@ def env():
     return torch, binding
 
 
-def run_gpu(env, layer, x, grid=0):
+def run_gpu(env, layer, x, grid=0, three_launches=False):
     torch, B = env
     lin = B.OwqLinear(layer, layout=TILE)
-    if grid:
-        B.owq_set_launch(lin.handle, grid)
+    if grid or three_launches:
+        # prefetch_depth = -1: passes of 32 tokens or fewer take the three-launch path too
+        B.owq_set_launch(lin.handle, grid, 0, 0, -1 if three_launches else 0)
     xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     y = lin(xd)
     torch.cuda.synchronize()
@@ -79,7 +80,11 @@ def test_small_layers_match_oracle(env, case):
     layer = make_layer(LayerSpec(name, d_in, d_out, bits, group, k, seed=zlib.crc32(name.encode()) % 10000))
     x = make_x(layer, batch)
     print(f"case {name}: d_in={d_in} d_out={d_out} bits={bits} group={group} k={k} batch={batch}", flush=True)
-    check(run_gpu(env, layer, x), owq_ref.owq_linear_layer(layer, x), name)
+    want = owq_ref.owq_linear_layer(layer, x)
+    check(run_gpu(env, layer, x), want, name)
+    if batch % 64 and batch % 64 <= 32:       # the last pass would take the one-launch kernel: three launches too
+        print("  three launches", flush=True)
+        check(run_gpu(env, layer, x, three_launches=True), want, name + " three launches")
 
 
 @pytest.mark.parametrize("grid", [1, 2, 3, 7, 12])
