@@ -36,7 +36,7 @@ typedef struct owq_layer_s *owq_handle_t; /* opaque; owned by the library until 
 typedef enum {
   OWQ_OK = 0,
   OWQ_ERR_NULL = 1,       /* a required pointer is NULL */
-  OWQ_ERR_SHAPE = 2,      /* d_out < 1, d_in < 1, or the packed layer would reach 4 GiB */
+  OWQ_ERR_SHAPE = 2,      /* d_out < 1, d_in < 1, the packed layer would reach 4 GiB, or a launch shape does not fit */
   OWQ_ERR_BITS = 3,       /* bits is neither 3 nor 4 */
   OWQ_ERR_GROUP = 4,      /* group_size is neither 0 nor a positive multiple of 128 */
   OWQ_ERR_CODE_RANGE = 5, /* a code at a non-weak column is >= 2^bits */
@@ -207,12 +207,22 @@ owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes);
  *   GEMV layout: row_tiles_per_wg >= 1; row_splits divides row_tiles_per_wg; waves_per_wg in
  *     [1, 8] divides nslab * row_splits; prefetch_depth in {2, 4, 8} (8 only with at most 4
  *     waves).
- *   Tile layout: waves_per_wg = 4 or 8; prefetch_depth must be 0.  row_splits = S > 0: every
+ *   Tile layout: waves_per_wg = 4 or 8.  row_splits = S > 0: every
  *     group of 64 * waves_per_wg rows is cut into S column ranges, one workgroup each
  *     (S <= d_in / 256; row_tiles_per_wg must be 0 or that number of workgroups).
  *     row_splits = 0 and row_tiles_per_wg = P > 0: the flattened (row group, 256-column step)
  *     sequence is cut into P equal ranges.  Both 0: the default for the chosen waves_per_wg.
  *     The number of workgroups is limited by the partial-result slots of the scratch area.
+ *     These three shape the three-launch path, which takes passes of more than 16 tokens.
+ *     prefetch_depth shapes the one-launch kernel for passes of few tokens: 0 = the library
+ *     uses it for passes of 16 tokens or fewer and chooses its work split; -1 = never use it;
+ *     S + 100 c with S in [1, 99], c in [0, 3] = use it for every pass of 32 tokens or fewer,
+ *     with every row tile's columns cut into S ranges (S <= d_in / 128) and, for c = 1, 2, 3,
+ *     1, 2 or 4 row tiles per workgroup (c = 0: the library chooses).  A shape that does not
+ *     fit a later call's number of tokens (the activations of a range must fit LDS) makes
+ *     that owq_linear return OWQ_ERR_SHAPE.  The kernel needs x 16-byte aligned, d_in a
+ *     multiple of 128, a group size of 128 * 2^n or none, and one task; other calls take the
+ *     three-launch path.
  */
 owq_status_t owq_set_launch(owq_handle_t h, int32_t row_tiles_per_wg, int32_t row_splits,
                             int32_t waves_per_wg, int32_t prefetch_depth);

@@ -95,6 +95,7 @@ static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_ha
     const int e = prepare_tile_kernels(g, lds_limit);
     if (e == (int)hipErrorInvalidValue) return OWQ_ERR_UNSUPPORTED;
     if (e != 0) return OWQ_ERR_HIP;
+    if (prepare_tile_small_kernels() != 0) return OWQ_ERR_HIP;
   } else {
     shape = default_shape(g, lds_limit);
     if (shape.rtw < 1) return OWQ_ERR_UNSUPPORTED;
@@ -165,6 +166,7 @@ static owq_status_t run_linear(owq_handle_t h, const TaskSets &tasks, const void
   const int herr = h->info.layout == OWQ_LAYOUT_TILE
                        ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_split, h->tile_waves, h->tile_small_split, tasks, x, y, batch, stream)
                        : launch_gemv(h->info, h->shape, h->dev, tasks, x, y, batch, stream);
+  if (herr == -2) return OWQ_ERR_SHAPE;     // a launch shape set by the caller does not fit this batch
   if (herr != 0) {
     h->info.last_hip_error = herr;
     return OWQ_ERR_HIP;
@@ -265,7 +267,7 @@ owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t
   if (!live(h)) return OWQ_ERR_HANDLE;
   if (h->info.layout == OWQ_LAYOUT_TILE) {
     // tile layout: workgroups of the main kernel, column ranges per row group, waves per workgroup
-    if (depth < -1 || (depth > 0 && !tile_small_split_ok(h->info, depth))) return OWQ_ERR_SHAPE;
+    if (depth < -1 || depth >= 400 || (depth % 100 > 0 && !tile_small_split_ok(h->info, depth % 100))) return OWQ_ERR_SHAPE;
     const int32_t wv = waves ? waves : h->tile_waves;
     if (wv != 4 && wv != 8) return OWQ_ERR_SHAPE;
     const int32_t lim = tile_grid_limit(h->info, wv);

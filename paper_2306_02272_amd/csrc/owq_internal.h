@@ -85,15 +85,16 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 // waves = waves per workgroup of the main kernel (4 or 8).
 // split > 0: grid = row groups x split, every row group cut into `split` column ranges;
 // split = 0: the flattened (row group, column step) sequence cut into `grid` equal ranges.
-// small_split: column ranges per row tile of the one-launch kernel that takes passes of 32
-// tokens or fewer (0 = the library's choice, -1 = never use that kernel).
+// small_shape: work split of the one-launch kernel that takes passes of 32 tokens or fewer
+// (0 = the library's choice, -1 = never use that kernel, else S + 100 c, see launch_tile_small).
 int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, int32_t small_split,
                 const TaskSets &tasks, const void *x, void *y, int32_t batch, void *stream);
 // The one-launch kernel for 32 tokens or fewer (defined in owq_tile_small.hip).  Returns a
 // hipError_t as int, or -1 when the layer, the split or the alignment of x does not fit it.
-int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t split, const void *x, void *y, int32_t ntok,
+int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, const void *x, void *y, int32_t ntok,
                       void *stream);
 bool tile_small_split_ok(const owq_layer_info_t &g, int32_t split);
+int prepare_tile_small_kernels();   // LDS opt-in
 void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split);
 int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves);
 int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit);   // LDS opt-in for grouped layers

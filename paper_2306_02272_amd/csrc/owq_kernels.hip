@@ -153,15 +153,6 @@ __device__ long long g_trace[4096 * 16];
 #define TRACE(slot) do { } while (0)
 #endif
 
-// Sum over the 16 lanes of a row of the wave (every lane gets the total), in a fixed order.
-__device__ __forceinline__ float row16_sum(float v) {
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false));   // lanes ^1
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false));   // lanes ^2
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, false));  // mirror in 8
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, false));  // mirror in 16
-  return v;
-}
-
 // Template parameters: code width; tiles in flight per wave; whether the layer has
 // weak columns; XN = how many 16-byte units of activations a thread fetches into
 // registers ahead of the weight stream (needs x 16-byte aligned and d_in a multiple of

@@ -712,10 +712,9 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t spl
   for (int32_t t0 = 0; t0 < batch; t0 += kScratchBatch) {
     const int ntok = batch - t0 < kScratchBatch ? batch - t0 : kScratchBatch;
     const int nt = ntok > 32 ? 2 : 1;
-    // few tokens, one task: one launch (forced by a split > 0 for any pass of 32 tokens or fewer)
-    if (ntok <= (small_split > 0 ? 32 : 8) && small_split >= 0 && tasks.task_id == nullptr) {
+    if (ntok <= 32 && small_split >= 0 && tasks.task_id == nullptr) {   // few tokens, one task: one launch
       const int r = launch_tile_small(g, blob, small_split, xp + (size_t)t0 * g.d_in, yp + (size_t)t0 * g.d_out, ntok, stream);
-      if (r > 0) return r;
+      if (r > 0 || r == -2) return r;
       if (r == 0) continue;
     }
     sa.x = xp + (size_t)t0 * g.d_in;

@@ -5,20 +5,23 @@
 // Quantization", section "Acceleration on Real Device"):
 //     y[n,i] = sum_{j not weak} s_ig (q_ij - z_ig) x[n,j]  +  sum_t Ww_it x[n, idx_t]
 //
-// With few tokens the layer is bound by its weight stream and by latency, so nothing is
-// staged through memory first.  A workgroup of four waves owns one tile of 32 rows and a
-// range of blocks of 128 columns; every wave takes a quarter of the range and streams it on
-// its own: codes go from registers straight into the A operand (a pair of codes is masked out
-// of a dword and OR-ed into the mantissas of 2^(10-o), giving 2^(10-o)+q exactly), the
-// activations come straight from x as the B operand (lane = token, eight consecutive
-// columns; the weak columns are cleared by select on the way).  A second matrix instruction
-// per k-step, whose A operand holds a row of ones and a row of the constants 2^(10-o),
-// yields per token sum x and sum 2^(10-o) x of the block in the same lanes as the
-// products, so that  tot += s (acc - sum c x - z sum x)  can follow every block.  The product
-// of the fp16 weak columns with the activations gathered at their indices is a few more
-// k-steps into the same accumulators.  The four waves add their results through LDS in a
-// fixed order; with more than one column range per row tile the sums go to memory and a
-// second small kernel adds them, again in a fixed order.  No atomics.
+// With few tokens the layer is bound by its weight stream and by latency, so the only thing
+// in flight in the main loop is that stream.  A workgroup of four waves owns RT row tiles of
+// 32 rows (RT = 1, 2 or 4) and a range of blocks of 128 columns, cut into 4 / RT slices: wave
+// = (row tile, slice).  At the start the workgroup copies the activations of its range into
+// LDS, in the order the matrix instruction reads them, gathers the activations at the weak
+// indices, and stages the scales of its rows and the weak masks of its blocks.
+// Then every wave streams its codes, several blocks ahead: a pair of codes is masked out of a
+// dword and OR-ed into the mantissas of 2^(10-o), giving the A operand 2^(10-o)+q exactly;
+// the B operand comes from LDS.  Before that, in a second pass over the staged activations,
+// the workgroup clears the weak columns (by select) and sums, per token and block, x and
+// c x (c = the constant 2^(10-o) of every column), so that tot += s (acc - sum c x - z sum x)
+// can follow every block; it runs while the matrix cores work on the next block, into other
+// accumulators.  The product of the fp16 weak columns with the gathered activations is a few
+// more k-steps into tot.
+// The waves of a row tile add their results through LDS in a fixed order; with more than one
+// column range per row tile the sums go to memory and a second small kernel adds them, again
+// in a fixed order.  No atomics.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -38,165 +41,246 @@ struct SmallArgs {
   const u32x4 *weak_w;         // [d_out_pad][kp/8] units
   const _Float16 *x;           // [ntok][d_in], 16-byte aligned, d_in a multiple of 128
   _Float16 *y;                 // [ntok][d_out]
-  float *part;                 // split > 1: [split][32][d_out_pad]
-  int d_in, d_out, d_out_pad, ntok, nbp, nblk, bpg, kp, split;
+  float *part;                 // split > 1: [split][ntok][d_out_pad]
+  int d_in, d_out, d_out_pad, n_rt, ntok, nbp, kp, split;
+  int blk_base, blk_rem;       // blocks per column range: range sp has blk_base + (sp < blk_rem) of them
+  int lg_bpg;                  // blocks per group of scales: 1 << lg_bpg (one scale per row: 30, a single group)
+  int lg_tok;                  // tokens are padded to 1 << lg_tok in LDS
+  int lg_rt;                   // row tiles per workgroup: 1 << lg_rt
 };
 
-template <int J> struct Buf {};   // tag: register buffer J of the blocks in flight
+template <int J> struct Buf {};   // tag: register buffer J of the blocks in flight, or k-step J
 template <int J> __device__ std::integral_constant<int, J> buf_index(Buf<J>);
 
 constexpr int kSmallWaves = 4;
-constexpr int kSmallSzUnits = 4;      // 16-byte units of scales a thread stages: 128 groups per workgroup
+constexpr int kSmallSzUnits = 2;      // 16-byte units of scales a thread stages: groups x row tiles <= 64
+constexpr int kSmallXUnits = 12;      // 16-byte units of activations a thread stages: blocks x padded tokens <= 192
 constexpr int kSmallRedUnits = 1024;  // LDS units of the waves' results: [4][16][64] floats
+constexpr int kSmallGather = 8;       // gathered activations a thread fetches at once: 2048 (weak column, token) pairs
+constexpr int kSmallLdsMax = 80 * 1024;   // two workgroups per compute unit
 
-template <int BITS, bool GROUPED>
+// Developer aid (build with -DOWQ_TRACE): per-wave time stamps of the kernel's phases.
+#ifdef OWQ_TRACE
+__device__ long long g_trace_small[4096 * 8];
+#define STRACE(slot) do { if (lane == 0) g_trace_small[(((blockIdx.y * gridDim.x + blockIdx.x) * kSmallWaves + w) & 4095) * 8 + (slot)] = (long long)wall_clock64(); } while (0)
+#else
+#define STRACE(slot) do { } while (0)
+#endif
+
+// grid (column ranges, groups of row tiles).  Layers with one scale per row run as one group of
+// scales that spans all blocks.
+template <int BITS>
 __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
   constexpr int CH = BITS == 3 ? 3 : 4;
-  constexpr int NB = 2;                   // blocks in flight per wave; refilled register by register as they are used
-  constexpr int WK = GROUPED ? 2 : 3;     // k-steps of weak columns a wave fetches ahead of its blocks (registers decide)
+  constexpr int NB = 6;                   // code buffers per wave: five blocks in flight behind the one in use
+  constexpr int WK = 2;                   // k-steps of weak columns whose weights a wave fetches ahead of its blocks
   extern __shared__ u32x4 lds[];
-  float *red = reinterpret_cast<float *>(lds);
-  f2_t *szl = reinterpret_cast<f2_t *>(lds + kSmallRedUnits);   // [groups of the workgroup][32 rows] (scale, zero)
 
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, kg = lane >> 5;
-  const int rt = blockIdx.x / a.split, sp = blockIdx.x - rt * a.split;
-  const int b0 = (int)((long long)a.nblk * sp / a.split), b1 = (int)((long long)a.nblk * (sp + 1) / a.split);
-  const int nbw = b1 - b0;                                      // >= 1: split <= nblk
-  const int wb0 = b0 + nbw * w / kSmallWaves, wb1 = b0 + nbw * (w + 1) / kSmallWaves;
-  const int g_lo = GROUPED ? b0 / a.bpg : 0;
-  const int ng = GROUPED ? (b1 - 1) / a.bpg - g_lo + 1 : 1;
-  u32x4 *wml = lds + kSmallRedUnits + ng * 16;                  // [blocks of the workgroup] 16 bytes of weak mask
-  const int n_c = n < a.ntok ? n : 0;                           // lanes without a token re-read token 0; never stored
-  const _Float16 *xrow = a.x + (size_t)n_c * a.d_in;
+  STRACE(0);
+  const int RT = 1 << a.lg_rt, KS = kSmallWaves >> a.lg_rt;
+  const int rtl = w & (RT - 1), ks = w >> a.lg_rt;
+  const int sp = blockIdx.x, rg = blockIdx.y;
+  const int b0 = sp * a.blk_base + (sp < a.blk_rem ? sp : a.blk_rem);
+  const int nbw = a.blk_base + (sp < a.blk_rem ? 1 : 0);       // >= 1: split <= number of blocks
+  const int b1 = b0 + nbw;
+  const int wb0 = b0 + ((nbw * ks) >> (2 - a.lg_rt)), wb1 = b0 + ((nbw * (ks + 1)) >> (2 - a.lg_rt));
+  const bool rt_ok = rg * RT + rtl < a.n_rt;                    // the last group of row tiles may be short
+  const int rt = rt_ok ? rg * RT + rtl : a.n_rt - 1;
 
-  // ---- (1) what the set-up needs: scales, weak masks, weak indices -------------------
-  // Issued before the weight stream: loads complete in order, so waiting for these does not
-  // wait for the weights behind them.  No branches: reads past the end are clamped and dropped.
-  u32x4 szv[kSmallSzUnits];
-#pragma unroll
-  for (int j = 0; j < kSmallSzUnits; ++j) {
-    const int i = tid + 256 * j, ic = i < ng * 8 ? i : 0;
-    szv[j] = *reinterpret_cast<const u32x4 *>(a.sz + (size_t)(g_lo + (ic >> 3)) * a.d_out_pad + rt * 32 + (ic & 7) * 4);
-  }
-  const u32x4 wmv = *reinterpret_cast<const u32x4 *>(a.wmask + (size_t)(b0 + (tid < nbw ? tid : 0)) * 16);
-  // weak columns: the k-steps are dealt out to all waves of the row tile's workgroups; the first
-  // WK of a wave ride ahead of its blocks
-  const int kunits = a.kp >> 3, ksteps = (kunits + 1) >> 1;
-  const bool weak_here = kunits > 0;
-  const int wslot = sp * kSmallWaves + w, wstride = a.split * kSmallWaves;
-  int widx[WK][8];
-#pragma unroll
-  for (int i = 0; i < WK; ++i) {
-    const int s = wslot + wstride * i;
-    const int u = 2 * s + kg, uc = (weak_here && u < kunits) ? u : 0;
-    const u32x4 *ip = reinterpret_cast<const u32x4 *>(a.weak_idx + 8 * uc);
-    const u32x4 lo = ip[0], hi = ip[1];
-    widx[i][0] = (int)lo.x; widx[i][1] = (int)lo.y; widx[i][2] = (int)lo.z; widx[i][3] = (int)lo.w;
-    widx[i][4] = (int)hi.x; widx[i][5] = (int)hi.y; widx[i][6] = (int)hi.z; widx[i][7] = (int)hi.w;
-  }
-
-  // ---- (2) the weight stream: NB blocks in flight per wave ----------------------------
+  // ---- (1) the first blocks of codes, then the loads of the set-up ------------------------
+  // Past the wave's range the code loads still go out (to a block that exists) and are dropped: the
+  // number of loads in flight is the same on every path and the waits can be exact.
   u32x4 cA[NB];
   u32x4 cB[NB];      // 4-bit: second chunk; 3-bit: .xy = the block's half of the middle chunk
-  u32x4 xb[NB][8];
-  // Past the wave's range the loads still go out (to a block that exists) and are dropped: the
-  // number of loads in flight is the same on every path.
+  const char *cbase = reinterpret_cast<const char *>(a.codes);
+  const u32 coff = ((u32)(rt * a.nbp) * (CH * 64) + (u32)lane) * 16u;      // byte offsets: the blob is below 4 GiB
   auto fetch_codes = [&](auto tag, int b) __attribute__((always_inline)) {
     constexpr int J = decltype(buf_index(tag))::value;
     const int bc = b < wb1 ? b : b0;
     const int bp = bc >> 1, h = bc & 1;
-    const u32x4 *t = a.codes + (size_t)(rt * a.nbp + bp) * CH * 64 + lane;
-    cA[J] = __builtin_nontemporal_load(t + 2 * h * 64);
+    const u32 t = coff + (u32)bp * (CH * 64 * 16);
+    cA[J] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(cbase + (t + (u32)(2 * h * 1024))));
     if (BITS == 4) {
-      cB[J] = __builtin_nontemporal_load(t + (2 * h + 1) * 64);
+      cB[J] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(cbase + (t + (u32)((2 * h + 1) * 1024))));
     } else {
-      const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(t + 64) + h);
+      const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(cbase + (t + (u32)(1024 + 8 * h))));
       cB[J].x = v.x; cB[J].y = v.y;
     }
   };
-  auto fetch_x = [&](auto tag, auto ks, int b) __attribute__((always_inline)) {
-    constexpr int J = decltype(buf_index(tag))::value;
-    constexpr int S = decltype(buf_index(ks))::value;
-    const int bc = b < wb1 ? b : b0;
-    xb[J][S] = *reinterpret_cast<const u32x4 *>(xrow + bc * 128 + 8 * kg + 16 * S);
-  };
-  auto fetch = [&](auto tag, int b) __attribute__((always_inline)) {
-    fetch_x(tag, Buf<0>{}, b); fetch_x(tag, Buf<1>{}, b); fetch_x(tag, Buf<2>{}, b); fetch_x(tag, Buf<3>{}, b);
-    fetch_x(tag, Buf<4>{}, b); fetch_x(tag, Buf<5>{}, b); fetch_x(tag, Buf<6>{}, b); fetch_x(tag, Buf<7>{}, b);
-    fetch_codes(tag, b);
-  };
-  fetch(Buf<0>{}, wb0);
-  fetch(Buf<1>{}, wb0 + 1);
-  if constexpr (NB == 3) fetch(Buf<2>{}, wb0 + 2);
+  fetch_codes(Buf<0>{}, wb0);
+  fetch_codes(Buf<1>{}, wb0 + 1);
+  fetch_codes(Buf<2>{}, wb0 + 2);
+  fetch_codes(Buf<3>{}, wb0 + 3);
+  fetch_codes(Buf<4>{}, wb0 + 4);
+  __builtin_amdgcn_sched_barrier(0);         // the weight stream goes out first
 
-  // ---- (3) set-up data to LDS; gathers of the weak columns ------------------------------
+  const int g_lo = b0 >> a.lg_bpg;
+  const int ng = ((b1 - 1) >> a.lg_bpg) - g_lo + 1;
+  const int np = 1 << a.lg_tok, nm = n & (np - 1);
+  const int kunits = a.kp >> 3, ksteps = (kunits + 1) >> 1;
+  // LDS map, in 16-byte units.  The waves' results reuse the room of the activations at the end.
+  const int nr = nbw * 16;                                      // octets of the workgroup's range
+  const int pitch = nr | 1;                                     // odd: the tokens of a k-step fall into different banks
+  const int npairs = nbw << a.lg_tok;                           // (block, token) pairs
+  u32x4 *xs = lds;                                              // [np tokens][pitch]: 8 activations per unit
+  float *red = reinterpret_cast<float *>(lds);                  // [4 waves][16][64]
+  f2_t *szl = reinterpret_cast<f2_t *>(lds + (np * pitch > kSmallRedUnits ? np * pitch : kSmallRedUnits));   // [groups][row tiles][32 rows]
+  u32x4 *xw = reinterpret_cast<u32x4 *>(szl) + ng * RT * 16;    // [kunits][np tokens] 8 gathered activations
+  unsigned short *xw_h = reinterpret_cast<unsigned short *>(xw);
+  f2_t *bs = reinterpret_cast<f2_t *>(xw + kunits * np);        // [blocks][np tokens] (sum x, sum c*x)
+
+  // Which of the staging loads go out depends on sizes only, the same for the whole workgroup.
+  // Gathers: element e = tid + 256 i is token e & (np - 1) and weak column e >> lg_tok.
+  const int tok = tid & (np - 1), r0 = tid >> a.lg_tok, rstep = 256 >> a.lg_tok;
+  const bool tok_ok = tok < a.ntok;
+  const u32 tok_off = (u32)(tok_ok ? tok : 0) * (u32)a.d_in;
+  int gj[kSmallGather];
+#pragma unroll
+  for (int i = 0; i < kSmallGather; ++i) {
+    const int t = r0 + i * rstep;
+    gj[i] = -1;
+    if (i * rstep < a.kp) gj[i] = a.weak_idx[(u32)(t < a.kp ? t : 0)];
+  }
+  u32x4 szv[kSmallSzUnits];
+#pragma unroll
+  for (int j = 0; j < kSmallSzUnits; ++j) {
+    const int i = tid + 256 * j, ic = i < ng * RT * 8 ? i : 0;
+    const int gq = (ic >> 3) >> a.lg_rt, rq = (ic >> 3) & (RT - 1);
+    int rtq = rg * RT + rq;
+    if (rtq > a.n_rt - 1) rtq = a.n_rt - 1;
+    szv[j] = *reinterpret_cast<const u32x4 *>(a.sz + (u32)((g_lo + gq) * a.d_out_pad + rtq * 32 + (ic & 7) * 4));
+  }
+  // Activations: 16 lanes take the 16 octets of a (block, token) pair; pair p = (tid >> 4) + 16 j is token
+  // p & (np - 1) of block p >> lg_tok.
+  const int o16 = tid & 15, pg = tid >> 4;
+  u32x4 xv[kSmallXUnits];
+  u32 xm[kSmallXUnits];         // the octet's byte of the weak mask
+#pragma unroll
+  for (int j = 0; j < kSmallXUnits; ++j) {
+    const int pr = pg + 16 * j, prc = pr < npairs ? pr : 0;
+    const int tk = prc & (np - 1), bl = prc >> a.lg_tok;
+    if (16 * j < npairs) {
+      xv[j] = *reinterpret_cast<const u32x4 *>(a.x + ((u32)(tk < a.ntok ? tk : 0) * (u32)a.d_in + (u32)((b0 + bl) * 128 + o16 * 8)));
+      xm[j] = a.wmask[(u32)((b0 + bl) * 16 + o16)];
+    }
+  }
+  // weak columns: the k-steps are dealt out to the waves of the row tile in all its workgroups;
+  // the weights of a wave's first WK k-steps ride ahead of its blocks
+  const int wslot = sp * KS + ks, wstride = a.split * KS;
+  u32x4 wa[WK];
+#pragma unroll
+  for (int i = 0; i < WK; ++i) {
+    const int u = 2 * (wslot + wstride * i) + kg;
+    wa[i] = a.weak_w[(u32)((rt * 32 + n) * kunits + (u < kunits ? u : 0))];
+  }
+  __builtin_amdgcn_sched_barrier(0);         // all of these are in flight before anything waits
+  STRACE(1);
+
+  // ---- (2) the gathers go out once their indices are there; scales and activations into LDS ---
+  // The gathered values stay in registers until the wave's blocks are done: nothing waits for them.
+  u32 gv[kSmallGather];     // one fp16 each, kept apart: packing them here would wait for the loads
+  u32 gok = 0u;
+  const unsigned short *xbits = reinterpret_cast<const unsigned short *>(a.x);
+#pragma unroll
+  for (int i = 0; i < kSmallGather; ++i) {
+    const int t = r0 + i * rstep;
+    const bool ok = t < a.kp && tok_ok && (u32)gj[i] < (u32)a.d_in;
+    gv[i] = xbits[ok ? tok_off + (u32)gj[i] : 0u];     // always issued: a load under a branch would be waited for there
+    gok |= ok ? (1u << i) : 0u;
+  }
 #pragma unroll
   for (int j = 0; j < kSmallSzUnits; ++j) {
     const int i = tid + 256 * j;
-    if (i < ng * 8) {
+    if (i < ng * RT * 8) {
       const u32 d[4] = {szv[j].x, szv[j].y, szv[j].z, szv[j].w};
       f4_t *dst = reinterpret_cast<f4_t *>(szl + i * 4);
       dst[0] = (f4_t){half_lo(d[0]), half_hi(d[0]), half_lo(d[1]), half_hi(d[1])};
       dst[1] = (f4_t){half_lo(d[2]), half_hi(d[2]), half_lo(d[3]), half_hi(d[3])};
     }
   }
-  if (tid < nbw) wml[tid] = wmv;
-  u32x4 wa[WK];
-  h8_t wg[WK];
-  u32 wok[WK];       // bit e: element e of the k-step is a real weak column
+  {
+    // constants 2^(10-o) of the pairs of this lane's octet: its k-step is o16 >> 1, whose place in the quad of 32 codes decides
+    float c0 = 0.f, c1 = 0.f, c2 = 0.f, c3 = 0.f;
 #pragma unroll
-  for (int i = 0; i < WK; ++i) {
-    const int s = wslot + wstride * i;
-    const int u = 2 * s + kg, uc = (weak_here && u < kunits) ? u : 0;
-    wa[i] = a.weak_w[(size_t)(rt * 32 + n) * kunits + uc];
-    wok[i] = 0u;
+    for (int q = 0; q < 4; ++q)
+      if (((o16 >> 1) & 3) == q) {
+        c0 = (float)(1 << (10 - pair_offset(BITS, q, 0))); c1 = (float)(1 << (10 - pair_offset(BITS, q, 1)));
+        c2 = (float)(1 << (10 - pair_offset(BITS, q, 2))); c3 = (float)(1 << (10 - pair_offset(BITS, q, 3)));
+      }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int j = widx[i][e];
-      const bool ok = (u32)j < (u32)a.d_in;
-      wg[i][e] = xrow[ok ? j : 0];
-      wok[i] |= ok ? (1u << e) : 0u;
+    for (int j = 0; j < kSmallXUnits; ++j) {
+      const int pr = pg + 16 * j;
+      if (16 * j < npairs) {                   // same for the whole workgroup
+        const int prc = pr < npairs ? pr : 0;
+        const int tk = prc & (np - 1), bl = prc >> a.lg_tok;
+        u32x4 v = tk < a.ntok ? xv[j] : (u32x4){0u, 0u, 0u, 0u};
+        // weak columns contribute nothing to the dense term
+        const u32 m = xm[j];
+        if (m != 0u) {
+          if (m & 0x01u) v.x &= 0xffff0000u;
+          if (m & 0x02u) v.x &= 0x0000ffffu;
+          if (m & 0x04u) v.y &= 0xffff0000u;
+          if (m & 0x08u) v.y &= 0x0000ffffu;
+          if (m & 0x10u) v.z &= 0xffff0000u;
+          if (m & 0x20u) v.z &= 0x0000ffffu;
+          if (m & 0x40u) v.w &= 0xffff0000u;
+          if (m & 0x80u) v.w &= 0x0000ffffu;
+        }
+        if (pr < npairs) xs[tk * pitch + bl * 16 + o16] = v;
+        // sum x and sum c*x over the block: the 16 octets sit in 16 neighbouring lanes
+        const float p0 = dot2(v.x, kOnes, 0.f), p1 = dot2(v.y, kOnes, 0.f), p2 = dot2(v.z, kOnes, 0.f), p3 = dot2(v.w, kOnes, 0.f);
+        const float sx = row16_sum((p0 + p1) + (p2 + p3));
+        const float sb = row16_sum(__builtin_fmaf(p3, c3, __builtin_fmaf(p2, c2, __builtin_fmaf(p1, c1, p0 * c0))));
+        if (o16 == 0 && pr < npairs) bs[prc] = (f2_t){sx, sb};
+      }
+      __builtin_amdgcn_sched_barrier(0);     // one unit at a time: interleaving them costs registers, not time
     }
   }
+  STRACE(2);
   __syncthreads();
+  STRACE(3);
 
-  // ---- (4) the wave's blocks ------------------------------------------------------------
+  // ---- (3) the wave's blocks ------------------------------------------------------------
   Magic M;
   M.init();
-  // A operand of the second instruction: rows 0 and 4 ones, rows 1 and 5 the constants
-  u32 cxm[8];
+  // Two accumulators per block (even and odd k-steps): two independent chains of matrix instructions.
+  f16_t acc0, acc1, acc2, acc3, tot;
 #pragma unroll
-  for (int o = 0; o < 8; ++o) {
-    const int cls = n < 8 ? (n & 3) : 3;
-    cxm[o] = cls == 0 ? kOnes : (cls == 1 ? M.m[o] : 0u);
-  }
-  f16_t acc, accx, tot;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { acc[r] = 0.f; accx[r] = 0.f; tot[r] = 0.f; }
+  for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; acc2[r] = 0.f; acc3[r] = 0.f; tot[r] = 0.f; }
   const f16_t zero16 = tot;
   int b = wb0;
-  int gi = GROUPED ? wb0 / a.bpg - g_lo : 0, gpos = GROUPED ? wb0 % a.bpg : 0;
+  const int bpg_mask = (1 << a.lg_bpg) - 1;
+  int gi = (wb0 >> a.lg_bpg) - g_lo, gpos = wb0 & bpg_mask;
+  int gi_prev = 0;
 
-  auto scale_in = [&](int g) __attribute__((always_inline)) {
-    // tot += s * (acc - sum c*x - z * sum x) with the staged (scale, zero) of group g
-    const float X = accx[0], Bc = accx[1];
+  // tot += s * (acc - sum c*x - z * sum x) with the staged (scale, zero) of group g and the sums of block bl
+  auto scale_in = [&](const f16_t &acc, const f16_t &accb, int g, int bl) __attribute__((always_inline)) {
+    const f2_t sums = bs[(bl << a.lg_tok) + nm];
+    const float X = sums.x, Bc = sums.y;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const f4_t *src = reinterpret_cast<const f4_t *>(szl + g * 32 + 8 * q + 4 * kg);
+      const f4_t *src = reinterpret_cast<const f4_t *>(szl + (g * RT + rtl) * 32 + 8 * q + 4 * kg);
       const f4_t s01 = src[0], s23 = src[1];
       const float sc[4] = {s01[0], s01[2], s23[0], s23[2]}, zp[4] = {s01[1], s01[3], s23[1], s23[3]};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float v = acc[4 * q + e] - Bc;
+        float v = (acc[4 * q + e] + accb[4 * q + e]) - Bc;
         v = __builtin_fmaf(-zp[e], X, v);
         tot[4 * q + e] = __builtin_fmaf(sc[e], v, tot[4 * q + e]);
       }
     }
   };
 
+  // One block out of code buffer J.  The block's products go to the accumulators of its parity,
+  // and the scaling of the previous block (the other accumulators) runs after the first k-steps
+  // have been issued, while the matrix cores work.
   auto step = [&](auto tag) __attribute__((always_inline)) {
     constexpr int J = decltype(buf_index(tag))::value;
+    // refill the buffer of the previous step (its registers are dead; the one in use is still
+    // being read) for the block NB - 1 ahead
+    fetch_codes(Buf<(J + NB - 1) % NB>{}, b + NB - 1);
     u32 wd[8];
     if (BITS == 4) {
       wd[0] = cA[J].x; wd[1] = cA[J].y; wd[2] = cA[J].z; wd[3] = cA[J].w;
@@ -207,100 +291,116 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
       wd[2] = h ? cA[J].x : cA[J].z; wd[3] = h ? cA[J].y : cA[J].w;
       wd[4] = h ? cA[J].z : cB[J].x; wd[5] = h ? cA[J].w : cB[J].y;
     }
-    const u32x4 wm = wml[b - b0];
-    const u32 wms[4] = {(u32)__builtin_amdgcn_readfirstlane((int)wm.x), (u32)__builtin_amdgcn_readfirstlane((int)wm.y),
-                        (u32)__builtin_amdgcn_readfirstlane((int)wm.z), (u32)__builtin_amdgcn_readfirstlane((int)wm.w)};
-    auto kstep = [&](auto ks) __attribute__((always_inline)) {
-      constexpr int S = decltype(buf_index(ks))::value;
-      u32x4 xv = xb[J][S];
-      const u32 m16 = (wms[S >> 1] >> (16 * (S & 1))) & 0xffffu;     // same for the whole wave
-      if (m16 != 0u) {
-        const u32 m = (m16 >> (8 * kg)) & 0xffu;
-        // weak columns contribute nothing to the dense term
-        if (m & 0x01u) xv.x &= 0xffff0000u;
-        if (m & 0x02u) xv.x &= 0x0000ffffu;
-        if (m & 0x04u) xv.y &= 0xffff0000u;
-        if (m & 0x08u) xv.y &= 0x0000ffffu;
-        if (m & 0x10u) xv.z &= 0xffff0000u;
-        if (m & 0x20u) xv.z &= 0x0000ffffu;
-        if (m & 0x40u) xv.w &= 0xffff0000u;
-        if (m & 0x80u) xv.w &= 0x0000ffffu;
-      }
-      const h8_t bo = __builtin_bit_cast(h8_t, xv);
+    const u32x4 *xb = xs + nm * pitch + (b - b0) * 16 + kg;
+    f16_t &acce = (J & 1) ? acc2 : acc0;     // even k-steps
+    f16_t &acco = (J & 1) ? acc3 : acc1;     // odd k-steps
+    auto kstep = [&](auto ks_tag) __attribute__((always_inline)) {
+      constexpr int S = decltype(buf_index(ks_tag))::value;
+      const h8_t bo = __builtin_bit_cast(h8_t, xb[2 * S]);
       const h8_t ao = a_operand<BITS, S>(wd, M);
-      const u32x4 cx = {cxm[pair_offset(BITS, S, 0)], cxm[pair_offset(BITS, S, 1)], cxm[pair_offset(BITS, S, 2)],
-                        cxm[pair_offset(BITS, S, 3)]};
-      const bool fresh = GROUPED && S == 0;
-      acc = mma(ao, bo, fresh ? zero16 : acc);
-      accx = mma(__builtin_bit_cast(h8_t, cx), bo, fresh ? zero16 : accx);
-      fetch_x(tag, ks, b + NB);                // the register is free: refill it for the block NB ahead
+      if (S & 1) acco = mma(ao, bo, S == 1 ? zero16 : acco);
+      else acce = mma(ao, bo, S == 0 ? zero16 : acce);
     };
-    kstep(Buf<0>{}); kstep(Buf<1>{}); kstep(Buf<2>{}); kstep(Buf<3>{});
-    kstep(Buf<4>{}); kstep(Buf<5>{}); kstep(Buf<6>{}); kstep(Buf<7>{});
-    if (GROUPED) {
-      scale_in(gi);
-      if (++gpos == a.bpg) { gpos = 0; ++gi; }
+    kstep(Buf<0>{}); kstep(Buf<1>{});
+    if (b > wb0) {
+      if (J & 1) scale_in(acc0, acc1, gi_prev, b - 1 - b0); else scale_in(acc2, acc3, gi_prev, b - 1 - b0);
     }
-    fetch_codes(tag, b + NB);
+    kstep(Buf<2>{}); kstep(Buf<3>{});
+    kstep(Buf<4>{}); kstep(Buf<5>{}); kstep(Buf<6>{}); kstep(Buf<7>{});
+    gi_prev = gi;
+    if (++gpos > bpg_mask) { gpos = 0; ++gi; }
     ++b;
+    __builtin_amdgcn_sched_barrier(0);         // blocks are scheduled one by one: mixing them costs registers
   };
+#pragma unroll 1
   while (b + NB <= wb1) {
     step(Buf<0>{});
     step(Buf<1>{});
-    if constexpr (NB == 3) step(Buf<2>{});
+    step(Buf<2>{});
+    step(Buf<3>{});
+    step(Buf<4>{});
+    step(Buf<5>{});
   }
   if (b < wb1) step(Buf<0>{});
-  if constexpr (NB == 3) {
-    if (b < wb1) step(Buf<1>{});
+  if (b < wb1) step(Buf<1>{});
+  if (b < wb1) step(Buf<2>{});
+  if (b < wb1) step(Buf<3>{});
+  if (b < wb1) step(Buf<4>{});
+  if (b > wb0) {                               // the last block's scaling
+    if ((b - 1 - wb0) & 1) scale_in(acc2, acc3, gi_prev, b - 1 - b0); else scale_in(acc0, acc1, gi_prev, b - 1 - b0);
   }
-  if (!GROUPED) scale_in(0);
+  STRACE(4);
 
-  // ---- (5) weak columns -----------------------------------------------------------------
-  if (weak_here) {
+  // ---- (4) weak columns -----------------------------------------------------------------
+  // element (weak column t, token) -> unit t >> 3 of the token, half t & 7
+#pragma unroll
+  for (int i = 0; i < kSmallGather; ++i) {
+    const int t = r0 + i * rstep;
+    if (t < a.kp) xw_h[(((t >> 3) << a.lg_tok) + tok) * 8 + (t & 7)] = ((gok >> i) & 1u) ? (unsigned short)gv[i] : (unsigned short)0;
+  }
+  for (int tb = kSmallGather * rstep; tb < a.kp; tb += kSmallGather * rstep) {     // many weak columns: further rounds
+    int j2[kSmallGather];
+#pragma unroll
+    for (int i = 0; i < kSmallGather; ++i) {
+      const int t = tb + r0 + i * rstep;
+      j2[i] = a.weak_idx[(u32)(t < a.kp ? t : 0)];
+    }
+    u32 v2[kSmallGather];
+#pragma unroll
+    for (int i = 0; i < kSmallGather; ++i) {
+      const int t = tb + r0 + i * rstep;
+      const bool ok = t < a.kp && tok_ok && (u32)j2[i] < (u32)a.d_in;
+      v2[i] = xbits[ok ? tok_off + (u32)j2[i] : 0u];
+      j2[i] = ok ? 1 : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < kSmallGather; ++i) {
+      const int t = tb + r0 + i * rstep;
+      if (t < a.kp) xw_h[(((t >> 3) << a.lg_tok) + tok) * 8 + (t & 7)] = j2[i] ? (unsigned short)v2[i] : (unsigned short)0;
+    }
+  }
+  STRACE(5);
+  __syncthreads();        // every wave is past its blocks: the room of the activations is free for the results
+  if (kunits > 0) {
     const u32x4 z4 = {0u, 0u, 0u, 0u};
+    const u32x4 *xwl = xw + nm;
 #pragma unroll
     for (int i = 0; i < WK; ++i) {
       const int s = wslot + wstride * i;
       if (s < ksteps) {                        // same for the whole wave
-        const bool uv = 2 * s + kg < kunits;
-        h8_t bo;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) bo[e] = (uv && ((wok[i] >> e) & 1u)) ? wg[i][e] : (_Float16)0;
-        tot = mma(__builtin_bit_cast(h8_t, uv ? wa[i] : z4), bo, tot);
+        const int u = 2 * s + kg;
+        const bool uv = u < kunits;
+        const u32x4 bv = xwl[(uv ? u : 0) << a.lg_tok];
+        tot = mma(__builtin_bit_cast(h8_t, uv ? wa[i] : z4), __builtin_bit_cast(h8_t, uv ? bv : z4), tot);
       }
     }
     for (int s = wslot + wstride * WK; s < ksteps; s += wstride) {    // many weak columns: no longer ahead
       const int u = 2 * s + kg;
       const bool uv = u < kunits;
-      const int uc = uv ? u : 0;
-      const u32x4 av = a.weak_w[(size_t)(rt * 32 + n) * kunits + uc];
-      h8_t bo;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int j = a.weak_idx[8 * uc + e];
-        const _Float16 v = xrow[(u32)j < (u32)a.d_in ? j : 0];
-        bo[e] = (uv && (u32)j < (u32)a.d_in) ? v : (_Float16)0;
-      }
-      tot = mma(__builtin_bit_cast(h8_t, uv ? av : z4), bo, tot);
+      const u32x4 av = a.weak_w[(u32)((rt * 32 + n) * kunits + (uv ? u : 0))];
+      const u32x4 bv = xwl[(uv ? u : 0) << a.lg_tok];
+      tot = mma(__builtin_bit_cast(h8_t, uv ? av : z4), __builtin_bit_cast(h8_t, uv ? bv : z4), tot);
     }
   }
+  STRACE(6);
 
-  // ---- (6) the four waves' results, added in a fixed order ----------------------------
+  // ---- (5) the results of the waves of a row tile, added in a fixed order ----------------
 #pragma unroll
   for (int r = 0; r < 16; ++r) red[(w * 16 + r) * 64 + lane] = tot[r];
   __syncthreads();
-  for (int e = tid; e < a.ntok * 32; e += 256) {
-    const int nn = e >> 5, row = e & 31;
+  for (int e = tid; e < (a.ntok << (5 + a.lg_rt)); e += 256) {
+    const int row = e & 31, rq = (e >> 5) & (RT - 1), nn = e >> (5 + a.lg_rt);
     const int r = 4 * (row >> 3) + (row & 3), ln = nn + 32 * ((row >> 2) & 1);
-    const float v = ((red[(0 * 16 + r) * 64 + ln] + red[(1 * 16 + r) * 64 + ln]) + red[(2 * 16 + r) * 64 + ln]) +
-                    red[(3 * 16 + r) * 64 + ln];
-    const int grow = rt * 32 + row;
+    float v = 0.f;
+    for (int q = 0; q < KS; ++q) v += red[(((q << a.lg_rt) + rq) * 16 + r) * 64 + ln];
+    const int grow = (rg * RT + rq) * 32 + row;
     if (a.split == 1) {
       if (grow < a.d_out) a.y[(size_t)nn * a.d_out + grow] = (_Float16)v;
-    } else {
-      a.part[(size_t)(sp * 32 + nn) * a.d_out_pad + grow] = v;
+    } else if (grow < a.d_out_pad) {
+      a.part[(size_t)(sp * a.ntok + nn) * a.d_out_pad + grow] = v;
     }
   }
+  STRACE(7);
 }
 
 // Adds the results of the column ranges of every row (fixed order) and rounds to fp16.
@@ -309,7 +409,13 @@ __global__ __launch_bounds__(256) void owq_tile_small_sum(const float *part, _Fl
   const int row = blockIdx.x * 256 + threadIdx.x, nn = blockIdx.y;
   if (row >= d_out || nn >= ntok) return;
   float v = 0.f;
-  for (int s = 0; s < split; ++s) v += part[(size_t)(s * 32 + nn) * d_out_pad + row];
+  int s = 0;
+  for (; s + 4 <= split; s += 4) {        // four loads in flight; the additions keep their order
+    const float p0 = part[(size_t)((s + 0) * ntok + nn) * d_out_pad + row], p1 = part[(size_t)((s + 1) * ntok + nn) * d_out_pad + row];
+    const float p2 = part[(size_t)((s + 2) * ntok + nn) * d_out_pad + row], p3 = part[(size_t)((s + 3) * ntok + nn) * d_out_pad + row];
+    v = (((v + p0) + p1) + p2) + p3;
+  }
+  for (; s < split; ++s) v += part[(size_t)(s * ntok + nn) * d_out_pad + row];
   y[(size_t)nn * d_out + row] = (_Float16)v;
 }
 
@@ -318,66 +424,114 @@ __global__ __launch_bounds__(256) void owq_tile_small_sum(const float *part, _Fl
 // ---------------------------------------------------------------------------
 typedef void (*small_fn)(const SmallArgs);
 
-static small_fn pick_small(int bits, bool grouped) {
-  if (bits == 3) return grouped ? owq_tile_small<3, true> : owq_tile_small<3, false>;
-  return grouped ? owq_tile_small<4, true> : owq_tile_small<4, false>;
-}
+static small_fn pick_small(int bits) { return bits == 3 ? owq_tile_small<3> : owq_tile_small<4>; }
 
 static int real_blocks(const owq_layer_info_t &g) { return (g.d_in + kBlockCols - 1) / kBlockCols; }
 
-// LDS bytes of the small-batch kernel with `split` column ranges per row tile; 0 = that split
-// does not fit the kernel's staging (groups or blocks per workgroup) or the room for partial sums.
-static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split) {
-  const int nblk = real_blocks(g);
-  if (split < 1 || split > nblk) return 0;
-  const int bpg = g.group_size ? g.group_size / kBlockCols : nblk;
-  int ng_max = 1, nbw_max = 1;
+static int log2_ceil(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
+
+// log2 of the blocks per group of scales (one scale per row: 30, a single group); -1 = not a power of two
+static int log2_bpg(const owq_layer_info_t &g) {
+  if (g.n_groups <= 1) return 30;
+  const int bpg = g.group_size / kBlockCols;
+  const int l = log2_ceil(bpg);
+  return (1 << l) == bpg ? l : -1;
+}
+
+// LDS bytes of the kernel for `split` column ranges per row tile, 1 << lg_rt row tiles per
+// workgroup and tokens padded to 1 << lg_tok; 0 = does not fit the kernel's staging (units per
+// thread), the LDS of two workgroups per compute unit or the room for partial sums.
+static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split, int lg_rt, int lg_tok) {
+  const int nblk = real_blocks(g), lb = log2_bpg(g);
+  if (split < 1 || split > nblk || lb < 0) return 0;
+  const int rt = 1 << lg_rt, np = 1 << lg_tok;
+  const int base = nblk / split, rem = nblk % split;
+  int ng_max = 1;
   for (int sp = 0; sp < split; ++sp) {
-    const int b0 = (int)((int64_t)nblk * sp / split), b1 = (int)((int64_t)nblk * (sp + 1) / split);
-    const int ng = g.n_groups > 1 ? (b1 - 1) / bpg - b0 / bpg + 1 : 1;
+    const int b0 = sp * base + (sp < rem ? sp : rem), b1 = b0 + base + (sp < rem ? 1 : 0);
+    const int ng = ((b1 - 1) >> lb) - (b0 >> lb) + 1;
     if (ng > ng_max) ng_max = ng;
-    if (b1 - b0 > nbw_max) nbw_max = b1 - b0;
   }
-  if (ng_max > kSmallSzUnits * 256 / 8 || nbw_max > 256) return 0;
+  const int nbw_max = base + (rem > 0 ? 1 : 0);
+  if (ng_max * rt * 8 > kSmallSzUnits * 256 || nbw_max * np > kSmallXUnits * 16) return 0;
   if (split > 1) {
     const TileScratch ts = tile_scratch(g);
     if ((uint64_t)split * 32 * g.d_out_pad * 4 > ts.total - ts.off_slots) return 0;
   }
-  return (kSmallRedUnits + ng_max * 16 + nbw_max) * 16;
+  const int xunits = np * ((nbw_max * 16) | 1);
+  // activations (or the waves' results), scales, gathered activations, sums per block and token
+  const int64_t units = (int64_t)(xunits > kSmallRedUnits ? xunits : kSmallRedUnits) + ng_max * rt * 16 + (int64_t)(g.kp / 8) * np +
+                        (nbw_max * np + 1) / 2;
+  if (units * 16 > kSmallLdsMax) return 0;
+  return (int32_t)(units * 16);
 }
 
-// Column ranges per row tile when the caller does not say: as few as fill the chip's 512
-// places for workgroups of four waves, weighing a workgroup's fixed cost (its first loads,
-// the set-up, the last sums) and the second launch against the blocks each wave streams.
-static int32_t small_default_split(const owq_layer_info_t &g) {
-  const int nblk = real_blocks(g);
+// Work split when the caller does not say: a rough model of the launch in microseconds (a
+// workgroup's fixed cost, the blocks each wave streams, the traffic of activations and of
+// partial sums, the second launch), minimised over the row tiles per workgroup and the ranges.
+static void small_default_shape(const owq_layer_info_t &g, int ntok, int32_t want_split, int want_lg_rt, int32_t *split,
+                                int *lg_rt) {
+  const int nblk = real_blocks(g), lg_tok = log2_ceil(ntok);
   double best = 0.0;
-  int32_t pick = 0;
-  for (int32_t s = 1; s <= 16 && s <= nblk; ++s) {
-    if (small_lds_bytes(g, s) == 0 || small_lds_bytes(g, s) > 65536) continue;
-    const double wgs = (double)g.n_rt * s;
-    const double rounds = wgs <= 512.0 ? 1.0 : wgs / 512.0;
-    const double per_wave = (double)((nblk + s - 1) / s + kSmallWaves - 1) / kSmallWaves;
-    const double cost = rounds * (per_wave + 6.0) + (s > 1 ? 6.0 : 0.0);
-    if (pick == 0 || cost < best) { best = cost; pick = s; }
+  *split = 0;
+  *lg_rt = 0;
+  for (int l = 2; l >= 0; --l) {
+    if (want_lg_rt >= 0 && l != want_lg_rt) continue;
+    const int rt = 1 << l, ks = kSmallWaves >> l;
+    const int n_rg = (g.n_rt + rt - 1) / rt;
+    for (int32_t s = 1; s <= 64 && s <= nblk; ++s) {
+      if (want_split > 0 && s != want_split) continue;
+      if (small_lds_bytes(g, s, l, lg_tok) == 0) continue;
+      const int64_t wgs = (int64_t)n_rg * s;
+      const double rounds = (double)((wgs + 511) / 512);      // 512 places: a few workgroups more cost a whole round
+      const double per_wave = (double)(((nblk + s - 1) / s + ks - 1) / ks);
+      const double x_mb = (double)wgs * ((double)nblk / s) * 128.0 * ntok * 2.0 / 1e6;
+      const double part_mb = s > 1 ? 2.0 * s * ntok * g.d_out * 4.0 / 1e6 : 0.0;
+      const double cost = rounds * (2.5 + 0.3 * per_wave) + x_mb / 6.0 + part_mb / 4.0 + (s > 1 ? 2.5 + 0.15 * s : 0.0);
+      if (*split == 0 || cost < best) { best = cost; *split = s; *lg_rt = l; }
+    }
   }
-  return pick;
 }
 
+// owq_set_launch: is this split possible at all (one token, any number of row tiles per workgroup)?
 bool tile_small_split_ok(const owq_layer_info_t &g, int32_t split) {
-  const int32_t lds = small_lds_bytes(g, split);
-  return lds > 0 && lds <= 65536;
+  for (int l = 0; l <= 2; ++l)
+    if (small_lds_bytes(g, split, l, 0) > 0) return true;
+  return false;
 }
 
-// One pass of up to 32 tokens.  split = 0: the default.  Returns a hipError_t as int, or -1 when
-// this layer (or this call's x) does not fit the kernel and the caller has to take the
-// three-launch path.
-int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t split, const void *x, void *y, int32_t ntok,
+int prepare_tile_small_kernels() {
+  for (int bits = 3; bits <= 4; ++bits) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_small(bits)),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kSmallLdsMax);
+    if (e != hipSuccess) return (int)e;
+  }
+  return (int)hipSuccess;
+}
+
+// Passes of more tokens than this take the three-launch path unless the caller sets a shape:
+// there the activations of a workgroup's range no longer fit LDS without many column ranges.
+constexpr int kSmallAutoTokens = 16;
+
+// One pass of up to 32 tokens.  shape = S + 100 c: S column ranges per row tile (0 = the
+// library's choice), c = 0: the library chooses the row tiles per workgroup, c = 1, 2, 3: 1, 2
+// or 4 of them.  Returns a hipError_t as int, -1 when this layer or the alignment of x does not
+// fit the kernel and the caller has to take the three-launch path, -2 when the caller asked
+// for a shape that does not fit this number of tokens.
+int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, const void *x, void *y, int32_t ntok,
                       void *stream) {
-  if (ntok < 1 || ntok > 32) return -1;
+  if (ntok < 1 || ntok > 32 || shape < 0 || (shape == 0 && ntok > kSmallAutoTokens)) return -1;
   if ((reinterpret_cast<uintptr_t>(x) & 15) != 0 || g.d_in % kBlockCols != 0) return -1;   // whole blocks, aligned rows
-  if (split == 0) split = small_default_split(g);
-  if (split < 1 || !tile_small_split_ok(g, split)) return -1;
+  if (log2_bpg(g) < 0) return -1;                                                            // groups of 2^n blocks
+  int32_t split = 0;
+  int lg_rt = 0;
+  small_default_shape(g, ntok, shape % 100, shape / 100 - 1, &split, &lg_rt);
+  if (split < 1) return shape > 0 ? -2 : -1;
+  const int lg_tok = log2_ceil(ntok);
   const TileScratch ts = tile_scratch(g);
   uint8_t *base = static_cast<uint8_t *>(blob);
   SmallArgs a;
@@ -389,13 +543,15 @@ int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t split, cons
   a.x = static_cast<const _Float16 *>(x);
   a.y = static_cast<_Float16 *>(y);
   a.part = reinterpret_cast<float *>(base + g.off_scratch + ts.off_slots);
-  a.d_in = g.d_in; a.d_out = g.d_out; a.d_out_pad = g.d_out_pad; a.ntok = ntok; a.nbp = g.nbp;
-  a.nblk = real_blocks(g);
-  a.bpg = g.group_size ? g.group_size / kBlockCols : a.nblk;
-  a.kp = g.kp; a.split = split;
+  a.d_in = g.d_in; a.d_out = g.d_out; a.d_out_pad = g.d_out_pad; a.n_rt = g.n_rt; a.ntok = ntok; a.nbp = g.nbp;
+  const int nblk = real_blocks(g);
+  a.blk_base = nblk / split; a.blk_rem = nblk % split;
+  a.lg_bpg = log2_bpg(g);
+  a.kp = g.kp; a.split = split; a.lg_tok = lg_tok; a.lg_rt = lg_rt;
+  const int n_rg = (g.n_rt + (1 << lg_rt) - 1) >> lg_rt;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL(pick_small(g.bits, g.n_groups > 1), dim3((unsigned)(g.n_rt * split), 1, 1), dim3(256, 1, 1),
-                     (size_t)small_lds_bytes(g, split), st, a);
+  hipLaunchKernelGGL(pick_small(g.bits), dim3((unsigned)split, (unsigned)n_rg, 1), dim3(256, 1, 1),
+                     (size_t)small_lds_bytes(g, split, lg_rt, lg_tok), st, a);
   if (split > 1)
     hipLaunchKernelGGL(owq_tile_small_sum, dim3((unsigned)((g.d_out + 255) / 256), (unsigned)ntok, 1), dim3(256, 1, 1), 0, st,
                        a.part, a.y, split, ntok, g.d_out, g.d_out_pad);
@@ -403,3 +559,9 @@ int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t split, cons
 }
 
 }  // namespace owq
+
+#ifdef OWQ_TRACE
+extern "C" int owq_debug_read_trace_small(long long *host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(owq::g_trace_small), sizeof(long long) * 4096 * 8);
+}
+#endif

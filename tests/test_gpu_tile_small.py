@@ -25,7 +25,8 @@ def env():
 
 
 def run_gpu(env, layer, x, split=0):
-    """split: column ranges per row tile (0 = the library's choice, -1 = the three-launch path)."""
+    """split: S + 100 c.  S = column ranges per row tile (0 = the library's choice); c = 0: the library
+    chooses the row tiles per workgroup, c = 1, 2, 3: 1, 2 or 4 of them.  -1 = the three-launch path."""
     torch, B = env
     lin = B.OwqLinear(layer, layout=TILE)
     if split:
@@ -49,17 +50,17 @@ def check(y_gpu, y_ref, what=""):
 CASES = [
     # name, d_in, d_out, bits, group, k, batch, split
     ("s3_ch", 1024, 96, 3, 0, 8, 16, 0),
-    ("s4_ch", 1024, 96, 4, 0, 8, 32, 0),
+    ("s4_ch", 1024, 96, 4, 0, 8, 32, 2),
     ("s3_b1", 512, 64, 3, 0, 4, 1, 0),
     ("s4_b1_one_block", 128, 40, 4, 0, 3, 1, 1),         # one block: three of the four waves have nothing
     ("s3_rows", 768, 600, 3, 0, 24, 5, 0),               # 19 row tiles, the last one ragged
     ("s3_g128", 2048, 130, 3, 128, 16, 4, 0),
     ("s4_g128", 2048, 130, 4, 128, 16, 16, 0),
-    ("s4_g256", 2048, 67, 4, 256, 5, 31, 0),
-    ("s3_g512", 2560, 300, 3, 512, 9, 17, 0),            # groups of four blocks
-    ("s3_g128_split3", 2560, 300, 3, 128, 9, 17, 3),     # 20 blocks in ranges of 6, 7, 7
+    ("s4_g256", 2048, 67, 4, 256, 5, 31, 4),
+    ("s3_g512", 2560, 300, 3, 512, 9, 17, 5),            # groups of four blocks
+    ("s3_g128_split3", 2560, 300, 3, 128, 9, 7, 3),      # 20 blocks in ranges of 6, 7, 7
     ("s4_g128_split5", 1280, 64, 4, 128, 40, 8, 5),      # two blocks per workgroup: half of the waves idle
-    ("s3_ch_split2", 3072, 100, 3, 0, 33, 32, 2),
+    ("s3_ch_split2", 3072, 100, 3, 0, 33, 8, 2),
     ("s3_split_max", 512, 64, 3, 0, 4, 2, 4),            # one block per workgroup
     ("s4_k0", 1536, 64, 4, 0, 0, 7, 0),
     ("s3_k0_split2", 1536, 64, 3, 128, 0, 7, 2),
@@ -67,6 +68,14 @@ CASES = [
     ("s4_many_weak_split2", 1024, 70, 4, 128, 500, 9, 2),
     ("s3_k_odd_units", 1024, 64, 3, 0, 24, 3, 0),        # kp = 24: the last weak k-step is half empty
     ("s3_one_row", 512, 1, 3, 0, 2, 3, 0),
+    ("s3_rows_rt1", 768, 600, 3, 0, 24, 5, 101),          # one row tile per workgroup, four slices of the columns
+    ("s3_rows_rt2", 768, 600, 3, 0, 24, 9, 202),          # two row tiles x two slices, two ranges; 19 row tiles: ragged
+    ("s3_rows_rt4", 768, 600, 3, 0, 24, 32, 303),         # four row tiles, no slices, three ranges
+    ("s4_g128_rt1", 2048, 130, 4, 128, 16, 16, 102),
+    ("s4_g128_rt2", 2048, 130, 4, 128, 16, 3, 201),
+    ("s4_g128_rt4", 2048, 130, 4, 128, 16, 32, 304),
+    ("s3_g256_rt4", 4096, 260, 3, 256, 41, 20, 300),
+    ("s4_wide", 8192, 64, 4, 128, 82, 16, 0),            # 64 blocks x 16 tokens: the ranges must be cut to fit LDS
     ("s3_tail_pass", 1024, 96, 3, 0, 8, 64 + 6, 0),      # 64 tokens by the three-launch path, 6 by this kernel
     ("s4_tail_pass_g", 1024, 96, 4, 128, 8, 128 + 32, 2),
 ]
@@ -90,7 +99,26 @@ def test_split_limits(env):
         B.owq_set_launch(lin.handle, 0, 0, 0, 5)           # more ranges than blocks
     with pytest.raises(B.OwqError):
         B.owq_set_launch(lin.handle, 0, 0, 0, -2)
+    with pytest.raises(B.OwqError):
+        B.owq_set_launch(lin.handle, 0, 0, 0, 401)
+    B.owq_set_launch(lin.handle, 0, 0, 0, 304)
     lin.close()
+
+
+def test_a_shape_that_does_not_fit_the_batch_is_an_error(env):
+    # one range of 24 blocks for 32 tokens is more than a workgroup stages; the library's own choice works
+    torch, B = env
+    layer = make_layer(LayerSpec("nofit", 3072, 64, 3, 0, 4, 3))
+    x = torch.from_numpy(make_x(layer, 32)).cuda()
+    lin = B.OwqLinear(layer, layout=TILE)
+    B.owq_set_launch(lin.handle, 0, 0, 0, 1)
+    with pytest.raises(B.OwqError):
+        lin(x)
+    B.owq_set_launch(lin.handle, 0, 0, 0, 300)         # the library chooses the ranges
+    y = lin(x)
+    torch.cuda.synchronize()
+    lin.close()
+    check(y.cpu().numpy(), owq_ref.owq_linear_layer(layer, x.cpu().numpy()), "nofit")
 
 
 def test_all_columns_weak_reproduces_fp16_matmul(env):
@@ -101,13 +129,13 @@ def test_all_columns_weak_reproduces_fp16_matmul(env):
     layer.spec = LayerSpec("allweak", d_in, d_out, 3, 0, d_in, 5)
     layer.weak_idx = np.arange(d_in, dtype=np.int32)
     layer.weak_w = w16
-    x = rng.normal(0, 1, size=(20, d_in)).astype(np.float16)
+    x = rng.normal(0, 1, size=(12, d_in)).astype(np.float16)
     want = x.astype(np.float64) @ w16.astype(np.float64).T
     check(run_gpu(env, layer, x), want, "allweak")
     check(run_gpu(env, layer, x, 2), want, "allweak split 2")
 
 
-@pytest.mark.parametrize("bits,group,split", [(3, 0, 1), (4, 0, 2), (3, 128, 2), (4, 128, 1)])
+@pytest.mark.parametrize("bits,group,split", [(3, 0, 102), (4, 0, 202), (3, 128, 302), (4, 128, 2)])
 def test_one_hot_probing_is_bit_exact(env, bits, group, split):
     # x = e_j, 32 columns per call, reads the whole effective matrix back through the kernel:
     # fp16(s*(q-z)) at dense positions, Ww at weak ones.
@@ -127,7 +155,7 @@ def test_one_hot_probing_is_bit_exact(env, bits, group, split):
     np.testing.assert_array_equal(y.cpu().numpy().view(np.uint16), want.view(np.uint16))
 
 
-@pytest.mark.parametrize("bits,group,d_in,split", [(3, 0, 4096, 1), (4, 128, 2048, 2), (3, 256, 1024, 1), (4, 0, 2048, 3)])
+@pytest.mark.parametrize("bits,group,d_in,split", [(3, 0, 4096, 108), (4, 128, 2048, 204), (3, 256, 1024, 302), (4, 0, 2048, 4)])
 def test_integer_inputs_are_bit_exact(env, bits, group, d_in, split):
     # s = 2^-m, integer z, x in {-1, 0, 1}: every partial sum is a small dyadic number,
     # fp32 accumulation is exact, so y must equal the rounded oracle result bit for bit.
