@@ -178,7 +178,8 @@ def main() -> int:
             traffic = None
     info = first[0].info()
     flops_per_step = sum(2 * batch * sp.d_out * (sp.d_in + sp.k) for sp in specs)
-    if layout == 1:
+    small = layout == 1 and batch <= 16 and not args.launch     # the one-launch kernel of the tile layout: bound by the weight stream
+    if layout == 1 and not small:
         # three kernels per call; the matrix kernel dominates.  The figure charges the whole call to it.
         tflops = flops_per_step / len(specs) / avg_launch_s / 1e12
         roofline = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -191,11 +192,13 @@ def main() -> int:
     else:
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                    "kernel": f"owq_gemv_kernel<{specs[0].bits},{info.prefetch_depth}>",
+                    "kernel": (f"owq_tile_small<{specs[0].bits}> (+ owq_tile_small_sum)" if small
+                               else f"owq_gemv_kernel<{specs[0].bits},{info.prefetch_depth}>"),
                     "avg_launch_us": round(avg_launch_s * 1e6, 3),
                     "bytes_per_launch": step_bytes // len(specs)}
     result = {
-        "metric": "effective HBM GB/s (% of peak) + us/call, 3-bit OWQ linear, batch 1",
+        # the headline metric; other workloads say their own code width and batch
+        "metric": f"effective HBM GB/s (% of peak) + us/call, {specs[0].bits}-bit OWQ linear, batch {batch}",
         "value": round(value, 1),
         "unit": "GB/s",
         "n_gpus": 1,

@@ -409,13 +409,16 @@ __global__ __launch_bounds__(256) void owq_tile_small_sum(const float *part, _Fl
   const int row = blockIdx.x * 256 + threadIdx.x, nn = blockIdx.y;
   if (row >= d_out || nn >= ntok) return;
   float v = 0.f;
-  int s = 0;
-  for (; s + 4 <= split; s += 4) {        // four loads in flight; the additions keep their order
-    const float p0 = part[(size_t)((s + 0) * ntok + nn) * d_out_pad + row], p1 = part[(size_t)((s + 1) * ntok + nn) * d_out_pad + row];
-    const float p2 = part[(size_t)((s + 2) * ntok + nn) * d_out_pad + row], p3 = part[(size_t)((s + 3) * ntok + nn) * d_out_pad + row];
-    v = (((v + p0) + p1) + p2) + p3;
+  const float *p0 = part + (size_t)nn * d_out_pad + row;
+  const size_t pitch = (size_t)ntok * d_out_pad;
+  for (int s0 = 0; s0 < split; s0 += 16) {        // sixteen loads in flight; the additions keep their order
+    float p[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) p[i] = p0[(size_t)(s0 + i < split ? s0 + i : s0) * pitch];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (s0 + i < split) v += p[i];
   }
-  for (; s < split; ++s) v += part[(size_t)(s * ntok + nn) * d_out_pad + row];
   y[(size_t)nn * d_out + row] = (_Float16)v;
 }
 
@@ -488,10 +491,11 @@ static void small_default_shape(const owq_layer_info_t &g, int ntok, int32_t wan
       if (small_lds_bytes(g, s, l, lg_tok) == 0) continue;
       const int64_t wgs = (int64_t)n_rg * s;
       const double rounds = (double)((wgs + 511) / 512);      // 512 places: a few workgroups more cost a whole round
-      const double per_wave = (double)(((nblk + s - 1) / s + ks - 1) / ks);
-      const double x_mb = (double)wgs * ((double)nblk / s) * 128.0 * ntok * 2.0 / 1e6;
+      const int nbw = (nblk + s - 1) / s;
+      const double per_wave = (double)((nbw + ks - 1) / ks);
       const double part_mb = s > 1 ? 2.0 * s * ntok * g.d_out * 4.0 / 1e6 : 0.0;
-      const double cost = rounds * (2.5 + 0.3 * per_wave) + x_mb / 6.0 + part_mb / 4.0 + (s > 1 ? 2.5 + 0.15 * s : 0.0);
+      // fitted to measurements of 5120x5120, 5120x13824 and 13824x5120 layers at 2 to 16 tokens
+      const double cost = rounds * (3.0 + 0.55 * per_wave + 0.02 * nbw * (1 << lg_tok)) + part_mb / 3.0 + (s > 1 ? 2.5 : 0.0);
       if (*split == 0 || cost < best) { best = cost; *split = s; *lg_rt = l; }
     }
   }
