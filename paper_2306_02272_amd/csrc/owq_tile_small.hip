@@ -476,8 +476,8 @@ static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split, int lg_
 // Work split when the caller does not say: a rough model of the launch in microseconds (a
 // workgroup's fixed cost, the blocks each wave streams, the traffic of activations and of
 // partial sums, the second launch), minimised over the row tiles per workgroup and the ranges.
-static void small_default_shape(const owq_layer_info_t &g, int ntok, int32_t want_split, int want_lg_rt, int32_t *split,
-                                int *lg_rt) {
+static double small_default_shape(const owq_layer_info_t &g, int ntok, int32_t want_split, int want_lg_rt, int32_t *split,
+                                  int *lg_rt) {
   const int nblk = real_blocks(g), lg_tok = log2_ceil(ntok);
   double best = 0.0;
   *split = 0;
@@ -499,6 +499,7 @@ static void small_default_shape(const owq_layer_info_t &g, int ntok, int32_t wan
       if (*split == 0 || cost < best) { best = cost; *split = s; *lg_rt = l; }
     }
   }
+  return best;
 }
 
 // owq_set_launch: is this split possible at all (one token, any number of row tiles per workgroup)?
@@ -533,8 +534,14 @@ int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, cons
   if (log2_bpg(g) < 0) return -1;                                                            // groups of 2^n blocks
   int32_t split = 0;
   int lg_rt = 0;
-  small_default_shape(g, ntok, shape % 100, shape / 100 - 1, &split, &lg_rt);
+  const double cost = small_default_shape(g, ntok, shape % 100, shape / 100 - 1, &split, &lg_rt);
   if (split < 1) return shape > 0 ? -2 : -1;
+  if (shape == 0) {
+    // Large layers stream so many blocks per wave that the three launches do as well or better: their
+    // time is about 15 us + 1 us per 4.2 MB of codes at these batch sizes (measured on 13 to 127 MB layers).
+    const double code_mb = (double)g.n_rt * g.nbp * 64 * g.chunks * 16 / 1e6;
+    if (cost * 1.15 >= 15.0 + code_mb / 4.2) return -1;
+  }
   const int lg_tok = log2_ceil(ntok);
   const TileScratch ts = tile_scratch(g);
   uint8_t *base = static_cast<uint8_t *>(blob);
