@@ -13,12 +13,14 @@
 // indices, and stages the scales of its rows and the weak masks of its blocks.
 // Then every wave streams its codes, several blocks ahead: a pair of codes is masked out of a
 // dword and OR-ed into the mantissas of 2^(10-o), giving the A operand 2^(10-o)+q exactly;
-// the B operand comes from LDS.  Before that, in a second pass over the staged activations,
-// the workgroup clears the weak columns (by select) and sums, per token and block, x and
-// c x (c = the constant 2^(10-o) of every column), so that tot += s (acc - sum c x - z sum x)
-// can follow every block; it runs while the matrix cores work on the next block, into other
-// accumulators.  The product of the fp16 weak columns with the gathered activations is a few
-// more k-steps into tot.
+// the B operand comes from LDS.  While staging, the workgroup also sums, per token and block,
+// X = sum x and C = sum c x (c = the constant 2^(10-o) of every column).  A ninth matrix
+// instruction per block, in bf16 (whose range is that of fp32), subtracts C + z X from the
+// accumulators: its A operand holds -1 and -z of the row (z in two exact bf16 pieces), its B
+// operand C and X of the token (three exact bf16 pieces each).  What is left per block is
+// tot += s acc, one operation per element, and it runs while the matrix cores work on the next
+// block, into the other accumulator.  The product of the fp16 weak columns with the gathered
+// activations is a few more k-steps into tot.
 // The waves of a row tile add their results through LDS in a fixed order; with more than one
 // column range per row tile the sums go to memory and a second small kernel adds them, again
 // in a fixed order.  No atomics.
@@ -32,6 +34,7 @@
 namespace owq {
 
 typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf8_t __attribute__((ext_vector_type(8)));
 
 struct SmallArgs {
   const u32x4 *codes;
@@ -126,10 +129,10 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
   const int npairs = nbw << a.lg_tok;                           // (block, token) pairs
   u32x4 *xs = lds;                                              // [np tokens][pitch]: 8 activations per unit
   float *red = reinterpret_cast<float *>(lds);                  // [4 waves][16][64]
-  f2_t *szl = reinterpret_cast<f2_t *>(lds + (np * pitch > kSmallRedUnits ? np * pitch : kSmallRedUnits));   // [groups][row tiles][32 rows]
+  f2_t *szl = reinterpret_cast<f2_t *>(lds + (np * pitch > kSmallRedUnits ? np * pitch : kSmallRedUnits));   // [groups][row tiles]: 32 scales, 32 zero points
   u32x4 *xw = reinterpret_cast<u32x4 *>(szl) + ng * RT * 16;    // [kunits][np tokens] 8 gathered activations
   unsigned short *xw_h = reinterpret_cast<unsigned short *>(xw);
-  f2_t *bs = reinterpret_cast<f2_t *>(xw + kunits * np);        // [blocks][np tokens] (sum x, sum c*x)
+  u32x4 *bs = xw + kunits * np;                                 // [blocks][np tokens][2]: B operand of the block's ninth instruction
 
   // Which of the staging loads go out depends on sizes only, the same for the whole workgroup.
   // Gathers: element e = tid + 256 i is token e & (np - 1) and weak column e >> lg_tok.
@@ -195,9 +198,10 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
     const int i = tid + 256 * j;
     if (i < ng * RT * 8) {
       const u32 d[4] = {szv[j].x, szv[j].y, szv[j].z, szv[j].w};
-      f4_t *dst = reinterpret_cast<f4_t *>(szl + i * 4);
-      dst[0] = (f4_t){half_lo(d[0]), half_hi(d[0]), half_lo(d[1]), half_hi(d[1])};
-      dst[1] = (f4_t){half_lo(d[2]), half_hi(d[2]), half_lo(d[3]), half_hi(d[3])};
+      // unit i = rows 4 (i & 7) .. + 3 of (group, row tile) i >> 3: 32 scales, then 32 zero points
+      float *dst = reinterpret_cast<float *>(szl) + (i >> 3) * 64 + (i & 7) * 4;
+      *reinterpret_cast<f4_t *>(dst) = (f4_t){half_lo(d[0]), half_lo(d[1]), half_lo(d[2]), half_lo(d[3])};
+      *reinterpret_cast<f4_t *>(dst + 32) = (f4_t){half_hi(d[0]), half_hi(d[1]), half_hi(d[2]), half_hi(d[3])};
     }
   }
   {
@@ -233,7 +237,20 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
         const float p0 = dot2(v.x, kOnes, 0.f), p1 = dot2(v.y, kOnes, 0.f), p2 = dot2(v.z, kOnes, 0.f), p3 = dot2(v.w, kOnes, 0.f);
         const float sx = row16_sum((p0 + p1) + (p2 + p3));
         const float sb = row16_sum(__builtin_fmaf(p3, c3, __builtin_fmaf(p2, c2, __builtin_fmaf(p1, c1, p0 * c0))));
-        if (o16 == 0 && pr < npairs) bs[prc] = (f2_t){sx, sb};
+        if (o16 == 0 && pr < npairs) {
+          // C = sb and X = sx in three bf16 pieces each (the top 16 bits of what is left: exact)
+          const u32 ch = __builtin_bit_cast(u32, sb) & 0xffff0000u;
+          const float cr = sb - __builtin_bit_cast(float, ch);
+          const u32 cm = __builtin_bit_cast(u32, cr) & 0xffff0000u;
+          const u32 cl = __builtin_bit_cast(u32, cr - __builtin_bit_cast(float, cm)) & 0xffff0000u;
+          const u32 xh = __builtin_bit_cast(u32, sx) & 0xffff0000u;
+          const float xr = sx - __builtin_bit_cast(float, xh);
+          const u32 xmid = __builtin_bit_cast(u32, xr) & 0xffff0000u;
+          const u32 xl = __builtin_bit_cast(u32, xr - __builtin_bit_cast(float, xmid)) & 0xffff0000u;
+          // k = 0..7: C_h C_m C_l X_h X_m X_l X_h X_m; k = 8: X_l
+          bs[2 * prc] = (u32x4){(ch >> 16) | cm, (cl >> 16) | xh, (xmid >> 16) | xl, (xh >> 16) | xmid};
+          bs[2 * prc + 1] = (u32x4){xl >> 16, 0u, 0u, 0u};
+        }
       }
       __builtin_amdgcn_sched_barrier(0);     // one unit at a time: interleaving them costs registers, not time
     }
@@ -245,37 +262,29 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
   // ---- (3) the wave's blocks ------------------------------------------------------------
   Magic M;
   M.init();
-  // Two accumulators per block (even and odd k-steps): two independent chains of matrix instructions.
-  f16_t acc0, acc1, acc2, acc3, tot;
+  f16_t acc0, acc1, tot;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; acc2[r] = 0.f; acc3[r] = 0.f; tot[r] = 0.f; }
+  for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; tot[r] = 0.f; }
   const f16_t zero16 = tot;
   int b = wb0;
   const int bpg_mask = (1 << a.lg_bpg) - 1;
   int gi = (wb0 >> a.lg_bpg) - g_lo, gpos = wb0 & bpg_mask;
   int gi_prev = 0;
 
-  // tot += s * (acc - sum c*x - z * sum x) with the staged (scale, zero) of group g and the sums of block bl
-  auto scale_in = [&](const f16_t &acc, const f16_t &accb, int g, int bl) __attribute__((always_inline)) {
-    const f2_t sums = bs[(bl << a.lg_tok) + nm];
-    const float X = sums.x, Bc = sums.y;
+  // tot += s * acc with the staged scales of group g
+  auto scale_in = [&](const f16_t &acc, int g) __attribute__((always_inline)) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const f4_t *src = reinterpret_cast<const f4_t *>(szl + (g * RT + rtl) * 32 + 8 * q + 4 * kg);
-      const f4_t s01 = src[0], s23 = src[1];
-      const float sc[4] = {s01[0], s01[2], s23[0], s23[2]}, zp[4] = {s01[1], s01[3], s23[1], s23[3]};
+      const f4_t sc = *reinterpret_cast<const f4_t *>(reinterpret_cast<const float *>(szl) + (g * RT + rtl) * 64 + 8 * q + 4 * kg);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float v = (acc[4 * q + e] + accb[4 * q + e]) - Bc;
-        v = __builtin_fmaf(-zp[e], X, v);
-        tot[4 * q + e] = __builtin_fmaf(sc[e], v, tot[4 * q + e]);
-      }
+      for (int e = 0; e < 4; ++e) tot[4 * q + e] = __builtin_fmaf(sc[e], acc[4 * q + e], tot[4 * q + e]);
     }
   };
 
-  // One block out of code buffer J.  The block's products go to the accumulators of its parity,
-  // and the scaling of the previous block (the other accumulators) runs after the first k-steps
-  // have been issued, while the matrix cores work.
+  // One block out of code buffer J: eight k-steps of codes, then the ninth instruction that
+  // takes sum c*x + z * sum x away.  The products go to the accumulator of the block's parity;
+  // the scaling of the previous block (the other accumulator) runs after the first k-steps have
+  // been issued, while the matrix cores work.
   auto step = [&](auto tag) __attribute__((always_inline)) {
     constexpr int J = decltype(buf_index(tag))::value;
     // refill the buffer of the previous step (its registers are dead; the one in use is still
@@ -292,21 +301,32 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
       wd[4] = h ? cA[J].z : cB[J].x; wd[5] = h ? cA[J].w : cB[J].y;
     }
     const u32x4 *xb = xs + nm * pitch + (b - b0) * 16 + kg;
-    f16_t &acce = (J & 1) ? acc2 : acc0;     // even k-steps
-    f16_t &acco = (J & 1) ? acc3 : acc1;     // odd k-steps
+    f16_t &acc = (J & 1) ? acc1 : acc0;
     auto kstep = [&](auto ks_tag) __attribute__((always_inline)) {
       constexpr int S = decltype(buf_index(ks_tag))::value;
       const h8_t bo = __builtin_bit_cast(h8_t, xb[2 * S]);
       const h8_t ao = a_operand<BITS, S>(wd, M);
-      if (S & 1) acco = mma(ao, bo, S == 1 ? zero16 : acco);
-      else acce = mma(ao, bo, S == 0 ? zero16 : acce);
+      acc = mma(ao, bo, S == 0 ? zero16 : acc);
     };
     kstep(Buf<0>{}); kstep(Buf<1>{});
     if (b > wb0) {
-      if (J & 1) scale_in(acc0, acc1, gi_prev, b - 1 - b0); else scale_in(acc2, acc3, gi_prev, b - 1 - b0);
+      if (J & 1) scale_in(acc0, gi_prev); else scale_in(acc1, gi_prev);
     }
     kstep(Buf<2>{}); kstep(Buf<3>{});
     kstep(Buf<4>{}); kstep(Buf<5>{}); kstep(Buf<6>{}); kstep(Buf<7>{});
+    {
+      // ninth instruction: A = (-1 -1 -1 -zh -zh -zh -zl -zl | -zl 0 ...) of this lane's row, zh + zl = z exactly
+      const float z = reinterpret_cast<const float *>(szl)[(gi * RT + rtl) * 64 + 32 + n];
+      const u32 zh = __builtin_bit_cast(u32, z) & 0xffff0000u;
+      const u32 zl = __builtin_bit_cast(u32, z - __builtin_bit_cast(float, zh)) & 0xffff0000u;
+      const u32 nzh = zh ^ 0x80000000u, nzl = zl ^ 0x80000000u;
+      const u32 m1 = 0xbf80u;                  // bf16 -1
+      u32x4 ae;
+      if (kg == 0) ae = (u32x4){m1 | (m1 << 16), m1 | nzh, (nzh >> 16) | nzh, (nzl >> 16) | nzl};
+      else ae = (u32x4){nzl >> 16, 0u, 0u, 0u};
+      const u32x4 be = bs[2 * (((b - b0) << a.lg_tok) + nm) + kg];
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8_t, ae), __builtin_bit_cast(bf8_t, be), acc, 0, 0, 0);
+    }
     gi_prev = gi;
     if (++gpos > bpg_mask) { gpos = 0; ++gi; }
     ++b;
@@ -327,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
   if (b < wb1) step(Buf<3>{});
   if (b < wb1) step(Buf<4>{});
   if (b > wb0) {                               // the last block's scaling
-    if ((b - 1 - wb0) & 1) scale_in(acc2, acc3, gi_prev, b - 1 - b0); else scale_in(acc0, acc1, gi_prev, b - 1 - b0);
+    if ((b - 1 - wb0) & 1) scale_in(acc1, gi_prev); else scale_in(acc0, gi_prev);
   }
   STRACE(4);
 
@@ -468,7 +488,7 @@ static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split, int lg_
   const int xunits = np * ((nbw_max * 16) | 1);
   // activations (or the waves' results), scales, gathered activations, sums per block and token
   const int64_t units = (int64_t)(xunits > kSmallRedUnits ? xunits : kSmallRedUnits) + ng_max * rt * 16 + (int64_t)(g.kp / 8) * np +
-                        (nbw_max * np + 1) / 2;
+                        2 * nbw_max * np;
   if (units * 16 > kSmallLdsMax) return 0;
   return (int32_t)(units * 16);
 }
