@@ -41,11 +41,15 @@ WORKLOADS = {
 }
 
 
-def algorithmic_bytes(spec, batch: int) -> int:
-    """Bytes one call has to move: codes + (scale, zero) + weak columns + indices + x + y."""
+def algorithmic_bytes(spec, batch: int, layout: int = 0) -> int:
+    """Bytes one call has to move: codes + (scale, zero) + weak columns + indices + x + y.
+    Storage-favoured layout (2): codes of the columns that are not weak only, and a dword of
+    weak-column bookkeeping per 8 input columns instead of the indices."""
     groups = 1 if spec.group_size == 0 else -(-spec.d_in // spec.group_size)
-    return (spec.d_out * spec.d_in * spec.bits // 8 + 4 * spec.d_out * groups + 2 * spec.d_out * spec.k
-            + 4 * spec.k + 2 * batch * (spec.d_in + spec.d_out))
+    cols = spec.d_in - spec.k if layout == 2 else spec.d_in
+    index_bytes = 4 * (-(-spec.d_in // 8)) if layout == 2 else 4 * spec.k
+    return (spec.d_out * cols * spec.bits // 8 + 4 * spec.d_out * groups + 2 * spec.d_out * spec.k
+            + index_bytes + 2 * batch * (spec.d_in + spec.d_out))
 
 
 def main() -> int:
@@ -55,7 +59,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="opt6.7b-ffn", choices=sorted(WORKLOADS))
     ap.add_argument("--batch", type=int, default=0, help="tokens per call (default: the workload's own)")
-    ap.add_argument("--layout", type=int, default=-1, help="0 = single-token layout, 1 = tile layout (default: the workload's own)")
+    ap.add_argument("--layout", type=int, default=-1, help="0 = single-token layout, 1 = tile layout, 2 = storage-favoured single-token layout (default: the workload's own)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: the K timed steps are one HIP graph launch; eager: K*layers launches from Python")
     ap.add_argument("--footprint-gb", type=float, default=1.5, help="total bytes of packed copies to rotate over")
@@ -90,7 +94,7 @@ def main() -> int:
 
     layers = [make_layer(s) for s in specs]
     xs_host = [make_x(L, batch) for L in layers]
-    bytes_per_layer = [algorithmic_bytes(s, batch) for s in specs]
+    bytes_per_layer = [algorithmic_bytes(s, batch, layout) for s in specs]
     step_bytes = sum(bytes_per_layer)
 
     # packed copies to rotate over

@@ -46,7 +46,7 @@ typedef enum {
   OWQ_ERR_HANDLE = 9,     /* not a live handle */
   OWQ_ERR_HIP = 10,       /* a HIP call failed; see owq_layer_info_t.last_hip_error */
   OWQ_ERR_UNSUPPORTED = 11, /* the layer needs more on-chip memory than one workgroup may use */
-  OWQ_ERR_LAYOUT = 12      /* layout is neither OWQ_LAYOUT_GEMV nor OWQ_LAYOUT_TILE */
+  OWQ_ERR_LAYOUT = 12      /* layout is none of OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT */
 } owq_status_t;
 
 #define OWQ_MAX_BATCH 65535
@@ -76,7 +76,7 @@ typedef struct {
   const uint16_t *zero;
   const int32_t *weak_idx;
   const uint16_t *weak_w;
-  int32_t layout;     /* OWQ_LAYOUT_GEMV (0) or OWQ_LAYOUT_TILE (1), see below */
+  int32_t layout;     /* OWQ_LAYOUT_GEMV (0), OWQ_LAYOUT_TILE (1) or OWQ_LAYOUT_COMPACT (2), see below */
 } owq_layer_desc_t;
 
 /*
@@ -88,9 +88,18 @@ typedef struct {
  * rounding; they differ in speed only.  The blob of the tile layout ends in a scratch area
  * (staged activations, sums, fp32 partial results) that owq_linear uses at run time, so that
  * the call needs neither an allocation nor a workspace argument.
+ * OWQ_LAYOUT_COMPACT is the storage-favoured format of the paper's appendix B.2 for the
+ * single-token kernel: the weak columns are taken out of the low-bit matrix (d_in - k columns
+ * are stored, in their original order, blocked as in OWQ_LAYOUT_GEMV), which saves
+ * bits * k * d_out / 8 bytes; the kernel moves the activations of the remaining columns
+ * together while it stages them.  One scale per row only (group_size = 0, else
+ * OWQ_ERR_GROUP).  One more section follows the weak indices: one dword per 8 input columns,
+ * low byte = which of them are weak (bit e = column 8i+e), upper 24 bits = the number of weak
+ * columns before column 8i; owq_layer_info_t.off_wmask is its offset.
  */
 #define OWQ_LAYOUT_GEMV 0
 #define OWQ_LAYOUT_TILE 1
+#define OWQ_LAYOUT_COMPACT 2
 
 /*
  * Geometry of the packed blob (format version 1) and the launch shape in use.

@@ -58,6 +58,16 @@ with these differences:
     bytes, n_rg = ceil(n_rt / 8): staged activations of 64 tokens, their sums per block
     and per column chunk, the activations at the weak columns, and fp32 partial results
     of 256 rows by 64 tokens each.
+
+Storage-favoured layout (layout = 2; appendix B.2 of the paper: the weak columns are taken
+out of the low-bit matrix).  One scale per row only.  The codes section holds the d_in - k
+columns that are not weak, in their original order, as a layout-0 matrix of nblk blocks,
+nblk = the smallest count n >= max(1, ceil((d_in - k) / 128)) and <= ceil(d_in / 128) with
+n / CW(n) <= ceil(d_in / 128) / CW(ceil(d_in / 128)), i.e. no more tiles per row tile than the
+full row has (zero columns fill up the last blocks);
+everything else as in layout 0.  One more section follows weak_idx:
+wmeta, one little-endian dword per 8 input columns: low byte = weak mask (bit e = column
+8i+e is weak), upper 24 bits = number of weak columns before column 8i.
 """
 from __future__ import annotations
 
@@ -138,7 +148,17 @@ def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int, layout: 
         return Geometry(d_out, d_in, bits, group_size, k, nblk, 1, TILE_ROWS, 64, nbp, n_rt,
                         d_out_pad, chunks, n_groups, kp, 0, off_sz, off_weak_w, off_weak_idx,
                         total, 1, nbp, off_wmask, off_scratch)
+    if layout == 2:
+        assert group_size == 0, "storage-favoured layout: one scale per row"
     nblk = -(-d_in // BLOCK)
+    if layout == 2:
+        # the stored columns, padded with zero columns up to the first block count that needs
+        # no more tiles per row tile than the full row
+        full_slabs = nblk // tile_shape(nblk)[0]
+        nb = -(-max(d_in - k, 1) // BLOCK)
+        while nb < nblk and nb // tile_shape(nb)[0] > full_slabs:
+            nb += 1
+        nblk = nb
     cw, r = tile_shape(nblk)
     nact = r * cw
     nslab = nblk // cw
@@ -152,6 +172,12 @@ def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int, layout: 
     off_weak_w = _align(off_sz + d_out_pad * n_groups * 4)
     off_weak_idx = _align(off_weak_w + d_out_pad * kp * 2)
     total = _align(off_weak_idx + kp * 4)
+    if layout == 2:
+        off_wmeta = total
+        total = _align(off_wmeta + -(-d_in // 8) * 4)
+        return Geometry(d_out, d_in, bits, group_size, k, nblk, cw, r, nact, nslab, n_rt,
+                        d_out_pad, chunks, n_groups, kp, off_codes, off_sz, off_weak_w,
+                        off_weak_idx, total, 2, 0, off_wmeta, 0)
     return Geometry(d_out, d_in, bits, group_size, k, nblk, cw, r, nact, nslab, n_rt,
                     d_out_pad, chunks, n_groups, kp, off_codes, off_sz, off_weak_w,
                     off_weak_idx, total)
@@ -185,10 +211,11 @@ def _lane_dwords(block_codes: np.ndarray, bits: int) -> np.ndarray:
 def pack_codes(codes: np.ndarray, geo: Geometry) -> np.ndarray:
     """uint8 [d_out, d_in] -> uint8 bytes of the codes section."""
     codes = np.asarray(codes, dtype=np.uint8)
-    assert codes.shape == (geo.d_out, geo.d_in)
+    # layout 2: the caller passes the stored columns only
+    assert codes.shape == (geo.d_out, geo.d_in - geo.k if geo.layout == 2 else geo.d_in)
     assert int(codes.max(initial=0)) < (1 << geo.bits)
     full = np.zeros((geo.d_out_pad, geo.nblk * BLOCK), dtype=np.uint8)
-    full[:geo.d_out, :geo.d_in] = codes
+    full[:geo.d_out, :codes.shape[1]] = codes
     if geo.layout == 1:
         # [rt, row, bp, b, t, kg, e] -> lanes [rt, bp, kg, row] with lane columns [b, t, e]
         t = full.reshape(geo.n_rt, TILE_ROWS, geo.nbp, 2, 8, 2, 8)
@@ -212,7 +239,9 @@ def pack_layer(codes, scale, zero, group_size, weak_idx, weak_w, bits, layout: i
     geo = geometry(d_out, d_in, bits, group_size, int(idx.size), layout)
     codes[:, idx] = 0
     blob = np.zeros(geo.total_bytes, dtype=np.uint8)
-    sec = pack_codes(codes, geo)
+    is_weak_col = np.zeros(d_in, dtype=bool)
+    is_weak_col[idx] = True
+    sec = pack_codes(codes[:, ~is_weak_col] if layout == 2 else codes, geo)
     blob[geo.off_codes:geo.off_codes + sec.size] = sec
 
     s_bits = np.asarray(scale, dtype=np.float16).view(np.uint16).astype(np.uint32)
@@ -239,6 +268,14 @@ def pack_layer(codes, scale, zero, group_size, weak_idx, weak_w, bits, layout: i
         is_weak = np.zeros(geo.nbp * 256, dtype=np.uint8)
         is_weak[idx] = 1
         b = np.packbits(is_weak.reshape(-1, 8), axis=1, bitorder="little").reshape(-1)
+        blob[geo.off_wmask:geo.off_wmask + b.size] = b
+    if geo.layout == 2:
+        padded = np.zeros(-(-d_in // 8) * 8, dtype=np.uint32)
+        padded[:d_in] = is_weak_col
+        per_unit = padded.reshape(-1, 8)
+        mask = (per_unit << np.arange(8, dtype=np.uint32)).sum(axis=1).astype(np.uint32)
+        before = np.concatenate([[0], np.cumsum(per_unit.sum(axis=1))[:-1]]).astype(np.uint32)
+        b = (mask | (before << np.uint32(8))).astype("<u4").view(np.uint8).reshape(-1)
         blob[geo.off_wmask:geo.off_wmask + b.size] = b
     return blob, geo
 
@@ -297,6 +334,15 @@ def unpack_codes(blob: np.ndarray, geo: Geometry) -> np.ndarray:
                       ((q >> np.uint32(16))[..., None] >> sh) & np.uint32(15)], axis=-1)
     blocks = c.astype(np.uint8).reshape(geo.n_rt, geo.nslab, geo.r, geo.cw, BLOCK)
     full = blocks.transpose(0, 2, 1, 3, 4).reshape(geo.d_out_pad, geo.nblk * BLOCK)
+    if geo.layout == 2:
+        # the stored columns go back to their places; weak columns read as 0
+        ix = np.frombuffer(np.asarray(blob, dtype=np.uint8).tobytes(), dtype="<i4", count=geo.kp,
+                           offset=geo.off_weak_idx)[:geo.k]
+        keep = np.ones(geo.d_in, dtype=bool)
+        keep[ix] = False
+        out = np.zeros((geo.d_out, geo.d_in), dtype=np.uint8)
+        out[:, keep] = full[:geo.d_out, :geo.d_in - geo.k]
+        return out
     return np.ascontiguousarray(full[:geo.d_out, :geo.d_in])
 
 

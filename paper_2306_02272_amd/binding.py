@@ -22,7 +22,7 @@ STATUS_NAMES = ["OWQ_OK", "OWQ_ERR_NULL", "OWQ_ERR_SHAPE", "OWQ_ERR_BITS", "OWQ_
 (OWQ_ERR_NULL, OWQ_ERR_SHAPE, OWQ_ERR_BITS, OWQ_ERR_GROUP, OWQ_ERR_CODE_RANGE, OWQ_ERR_INDEX,
  OWQ_ERR_BUFFER, OWQ_ERR_BATCH, OWQ_ERR_HANDLE, OWQ_ERR_HIP, OWQ_ERR_UNSUPPORTED,
  OWQ_ERR_LAYOUT) = range(1, 13)
-OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE = 0, 1
+OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT = 0, 1, 2
 
 # every symbol include/owq.h declares
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",

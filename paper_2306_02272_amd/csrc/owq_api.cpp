@@ -43,9 +43,19 @@ owq_status_t owq_unpack_codes(const void *host_packed, const owq_layer_info_t *i
   owq_status_t st = compute_geometry(info->d_out, info->d_in, info->bits, info->group_size, info->k, info->layout, &g);
   if (st != OWQ_OK) return st;
   const uint32_t *dwords = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(host_packed) + g.off_codes);
+  const uint32_t *wmeta = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(host_packed) + g.off_wmask);
   for (int32_t row = 0; row < g.d_out; ++row) {
     const int32_t rt = row / g.r, rloc = row % g.r;
-    for (int32_t j = 0; j < g.d_in; ++j) {
+    for (int32_t jin = 0; jin < g.d_in; ++jin) {
+      int32_t j = jin;             // stored column
+      if (g.layout == OWQ_LAYOUT_COMPACT) {
+        const uint32_t meta = wmeta[jin >> 3], m = meta & 0xffu;
+        if ((m >> (jin & 7)) & 1u) {          // weak columns are not stored: code 0
+          codes[(int64_t)row * g.d_in + jin] = 0;
+          continue;
+        }
+        j = jin - (int32_t)((meta >> 8) + (uint32_t)__builtin_popcount(m & ((1u << (jin & 7)) - 1u)));
+      }
       int32_t cin, lane;
       int64_t tile;
       if (g.layout == OWQ_LAYOUT_TILE) {
@@ -77,7 +87,7 @@ owq_status_t owq_unpack_codes(const void *host_packed, const owq_layer_info_t *i
         const int64_t unit = (tile * g.chunks + v / 4) * g.nact + lane;
         code = (dwords[unit * 4 + (v & 3)] >> bit) & 15u;
       }
-      codes[(int64_t)row * g.d_in + j] = (uint8_t)code;
+      codes[(int64_t)row * g.d_in + jin] = (uint8_t)code;
     }
   }
   return OWQ_OK;
@@ -117,6 +127,7 @@ static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_ha
   h->dev.sz = base + g.off_sz;
   h->dev.weak_w = base + g.off_weak_w;
   h->dev.weak_idx = base + g.off_weak_idx;
+  h->dev.wmeta = base + g.off_wmask;
   h->info.last_hip_error = 0;
   *out = h;
   return OWQ_OK;

@@ -67,6 +67,7 @@ LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit);
 // Device-side launch (defined in owq_kernels.hip).  Returns a hipError_t as int.
 struct DeviceLayer {
   const void *codes, *sz, *weak_w, *weak_idx;
+  const void *wmeta;   // storage-favoured layout: weak mask and weak columns before, per 8 input columns
 };
 // Several sets of weak columns for one dense matrix (all DEVICE memory): token n uses
 // weak_sets[task_id[n]] when that index is in [0, n_sets), else the layer's own columns.

@@ -41,6 +41,9 @@ struct GemvArgs {
   const void *const *weak_sets;
   const int *task_id;
   int n_sets;
+  // storage-favoured layout: per 8 input columns, weak mask | weak columns before << 8; d_dense = stored columns
+  const u32 *wmeta;
+  int d_dense;
   int xper;   // 16-byte activation units per thread (ceil)
   // host-made reciprocals: n / d == (n * magic) >> 16 for the small n that occur (checked on the host)
   u32 cw_magic, nslab_magic, rsplit_magic, bpg_magic;
@@ -159,7 +162,9 @@ __device__ long long g_trace[4096 * 16];
 // 8; 0 = general path with scalar loads).  Units beyond XN per thread follow in a loop.
 // With 8 tiles in flight a wave needs the register file of a whole SIMD: at most 4 waves
 // per workgroup then.
-template <int BITS, int DEPTH, bool HAS_WEAK, int XN>
+// COMPACT: the layer stores only the columns that are not weak (storage-favoured layout): the
+// staging moves their activations together and drops the weak ones into their own array.
+template <int BITS, int DEPTH, bool HAS_WEAK, int XN, bool COMPACT = false>
 __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const GemvArgs a) {
   constexpr int CH = BITS == 3 ? 3 : 4;
   constexpr bool FAST = XN > 0;
@@ -203,6 +208,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   // end re-read unit 0 and are dropped below, so that the number of loads in
   // flight is fixed and the waits can be exact.
   uint4 xv[XCH];
+  u32 wmv[XCH];
   int idx0 = -1;
   if (FAST) {
 #pragma unroll
@@ -210,9 +216,10 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
       const int i = tid + j * nthr;
       const int ic = (i * 8 < a.d_in) ? i : 0;
       xv[j] = *reinterpret_cast<const uint4 *>(xn + ic * 8);
+      if (COMPACT) wmv[j] = a.wmeta[ic];
     }
   }
-  if (HAS_WEAK) idx0 = a.weak_idx[tid < a.kp ? tid : 0];
+  if (HAS_WEAK && !COMPACT) idx0 = a.weak_idx[tid < a.kp ? tid : 0];
 
   // ---- (2) per-item state and the tile pipeline ---------------------------------
   u32x4 buf[DEPTH][CH];
@@ -271,7 +278,66 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   TRACE(1);
 
   // ---- (3) activations -> LDS, transposed to [unit-in-block][block] -------------
-  if (FAST) {
+  if (COMPACT) {
+    // Column j goes to stored column j - (weak columns before j), or, if weak, to element
+    // (weak columns before j) of the weak activations.  Units without a weak column whose
+    // shift is a multiple of 8 move whole.
+    auto place = [&](int i, const uint4 &v, u32 meta) {
+      const u32 m = meta & 0xffu;
+      const int r = (int)(meta >> 8);
+      if (m == 0u && (r & 7) == 0 && i * 8 + 8 <= a.d_in) {
+        const int u = i - (r >> 3);
+        xs[(u & 15) * a.xpitch + (u >> 4)] = v;
+        return;
+      }
+      const u32 w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (i * 8 + e >= a.d_in) continue;
+        const unsigned short h = (unsigned short)(w4[e >> 1] >> (16 * (e & 1)));
+        const int rr = r + __builtin_popcount(m & ((1u << e) - 1u));
+        unsigned short *dst;
+        if ((m >> e) & 1u) {
+          dst = reinterpret_cast<unsigned short *>(xw) + rr;
+        } else {
+          const int c = i * 8 + e - rr, u = c >> 3;
+          dst = reinterpret_cast<unsigned short *>(xs_h) + (((u & 15) * a.xpitch + (u >> 4)) * 8 + (c & 7));
+        }
+        *dst = h;
+      }
+    };
+    for (int c = a.d_dense + tid; c < a.nblk * 128; c += nthr) {      // past the last stored column
+      const int u = c >> 3;
+      xs_h[((u & 15) * a.xpitch + (u >> 4)) * 8 + (c & 7)] = (_Float16)0;
+    }
+    for (int t = a.k + tid; t < a.kp; t += nthr) xw[t] = (_Float16)0;
+    if (FAST) {
+#pragma unroll
+      for (int j = 0; j < XCH; ++j) {
+        const int i = tid + j * nthr;
+        if (i * 8 < a.d_in) place(i, xv[j], wmv[j]);
+      }
+      for (int i = tid + XCH * nthr; i * 8 < a.d_in; i += nthr)         // very wide layers only
+        place(i, *reinterpret_cast<const uint4 *>(xn + i * 8), a.wmeta[i]);
+    } else {
+      const bool vec = ((reinterpret_cast<uintptr_t>(xn) & 15) == 0) && ((a.d_in & 7) == 0);
+      for (int i = tid; i * 8 < a.d_in; i += nthr) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (vec) {
+          v = *reinterpret_cast<const uint4 *>(xn + i * 8);
+        } else {
+          _Float16 e[8];
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            const int j = i * 8 + t;
+            e[t] = j < a.d_in ? xn[j] : (_Float16)0;
+          }
+          v = *reinterpret_cast<const uint4 *>(e);
+        }
+        place(i, v, a.wmeta[i]);
+      }
+    }
+  } else if (FAST) {
 #pragma unroll
     for (int j = 0; j < XCH; ++j) {
       const int i = tid + j * nthr;
@@ -307,7 +373,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   // Move the activations of the weak columns to their own array and clear them in
   // the staged copy: the dense path must contribute nothing there.  The index list
   // is the only layer data this waits for, and it is small.
-  if (HAS_WEAK) {
+  if (HAS_WEAK && !COMPACT) {
     auto gather = [&](int t, int j) {
       _Float16 v = (_Float16)0;
       if (j >= 0) {
@@ -434,31 +500,38 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 
 typedef void (*kernel_fn)(const GemvArgs);
 
-template <int BITS, int DEPTH, bool WEAK>
+template <int BITS, int DEPTH, bool WEAK, bool COMPACT>
 static kernel_fn pick3(int xn) {
-  if (xn == 4) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4>;
-  if (xn == 8) return owq_gemv_kernel<BITS, DEPTH, WEAK, 8>;
-  return owq_gemv_kernel<BITS, DEPTH, WEAK, 0>;
+  if (xn == 4) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, COMPACT>;
+  if (xn == 8) return owq_gemv_kernel<BITS, DEPTH, WEAK, 8, COMPACT>;
+  return owq_gemv_kernel<BITS, DEPTH, WEAK, 0, COMPACT>;
 }
 
+// The storage-favoured layout always runs the variant with weak columns (k = 0 stores the same
+// bytes as the other layout and takes the same kernel as it).
 template <int BITS>
-static kernel_fn pick2(int depth, bool weak, int xn) {
-  if (depth == 2) return weak ? pick3<BITS, 2, true>(xn) : pick3<BITS, 2, false>(xn);
-  if (depth == 4) return weak ? pick3<BITS, 4, true>(xn) : pick3<BITS, 4, false>(xn);
-  return weak ? pick3<BITS, 8, true>(xn) : pick3<BITS, 8, false>(xn);
+static kernel_fn pick2(int depth, bool weak, int xn, bool compact) {
+  if (compact) {
+    if (depth == 2) return pick3<BITS, 2, true, true>(xn);
+    if (depth == 4) return pick3<BITS, 4, true, true>(xn);
+    return pick3<BITS, 8, true, true>(xn);
+  }
+  if (depth == 2) return weak ? pick3<BITS, 2, true, false>(xn) : pick3<BITS, 2, false, false>(xn);
+  if (depth == 4) return weak ? pick3<BITS, 4, true, false>(xn) : pick3<BITS, 4, false, false>(xn);
+  return weak ? pick3<BITS, 8, true, false>(xn) : pick3<BITS, 8, false, false>(xn);
 }
 
-static kernel_fn pick(int bits, int depth, bool weak, int xn) {
-  return bits == 3 ? pick2<3>(depth, weak, xn) : pick2<4>(depth, weak, xn);
+static kernel_fn pick(int bits, int depth, bool weak, int xn, bool compact = false) {
+  return bits == 3 ? pick2<3>(depth, weak, xn, compact) : pick2<4>(depth, weak, xn, compact);
 }
 
 int prepare_kernels(int32_t lds) {
   if (lds <= 64 * 1024) return (int)hipSuccess;
   for (int bits = 3; bits <= 4; ++bits)
     for (int depth = 2; depth <= 8; depth *= 2)
-      for (int w = 0; w < 2; ++w)
+      for (int w = 0; w < 3; ++w)            // without weak columns, with, storage-favoured
         for (int xn = 0; xn <= 8; xn += 4) {
-          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(bits, depth, w, xn)),
+          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(bits, depth, w != 0, xn, w == 2)),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds);
           if (e != hipSuccess) return (int)e;
         }
@@ -494,7 +567,12 @@ int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLay
   a.xpitch = s.xpitch;
   a.ppitch = g.nblk;
   const int nthr = s.waves * 64;
-  a.xper = (g.nblk * 16 + nthr - 1) / nthr;
+  const bool compact = g.layout == OWQ_LAYOUT_COMPACT && g.kp > 0;
+  a.wmeta = static_cast<const u32 *>(dev.wmeta);
+  a.d_dense = g.d_in - g.k;
+  // units a thread stages: the stored blocks, or (storage-favoured) the wider input row
+  const int units = compact && (g.d_in + 7) / 8 > g.nblk * 16 ? (g.d_in + 7) / 8 : g.nblk * 16;
+  a.xper = (units + nthr - 1) / nthr;
   a.cw_magic = s.cw_magic; a.nslab_magic = s.nslab_magic; a.rsplit_magic = s.rsplit_magic;
   a.bpg_magic = s.bpg_magic;
   // 16-byte staging from registers needs aligned rows
@@ -502,7 +580,7 @@ int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLay
   const int xn = !aligned ? 0 : (a.xper <= 4 ? 4 : 8);
   const dim3 grid((unsigned)s.nwg, (unsigned)batch, 1), block((unsigned)nthr, 1, 1);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  kernel_fn fn = pick(g.bits, s.depth, g.kp > 0, xn);
+  kernel_fn fn = pick(g.bits, s.depth, g.kp > 0, xn, compact);
   hipLaunchKernelGGL(fn, grid, block, s.lds_bytes, st, a);
   return (int)hipGetLastError();
 }

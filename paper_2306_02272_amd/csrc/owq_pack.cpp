@@ -36,7 +36,8 @@ owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t
   if (bits != 3 && bits != 4) return OWQ_ERR_BITS;
   if (group_size < 0 || (group_size != 0 && group_size % kBlockCols != 0)) return OWQ_ERR_GROUP;
   if (k < 0 || k > d_in) return OWQ_ERR_INDEX;
-  if (layout != OWQ_LAYOUT_GEMV && layout != OWQ_LAYOUT_TILE) return OWQ_ERR_LAYOUT;
+  if (layout != OWQ_LAYOUT_GEMV && layout != OWQ_LAYOUT_TILE && layout != OWQ_LAYOUT_COMPACT) return OWQ_ERR_LAYOUT;
+  if (layout == OWQ_LAYOUT_COMPACT && group_size != 0) return OWQ_ERR_GROUP;
   std::memset(g, 0, sizeof(*g));
   g->format_version = OWQ_FORMAT_VERSION;
   g->d_out = d_out; g->d_in = d_in; g->bits = bits; g->group_size = group_size; g->k = k;
@@ -63,12 +64,26 @@ owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t
     if (g->total_bytes >= (1ull << 32)) return OWQ_ERR_SHAPE;
     return OWQ_OK;
   }
-  g->nblk = (d_in + kBlockCols - 1) / kBlockCols;
-  // Tile width: as many blocks of a row side by side as the wave can hold while
+  // Tile width of a row of nb blocks: as many blocks side by side as the wave can hold while
   // keeping at least 60 of its 64 lanes busy.
-  int cw = 1;
-  for (int c = 1; c <= 64 && c <= g->nblk; ++c)
-    if (g->nblk % c == 0 && (64 / c) * c >= 60) cw = c;
+  auto tile_width = [](int32_t nb) {
+    int c1 = 1;
+    for (int c = 1; c <= 64 && c <= nb; ++c)
+      if (nb % c == 0 && (64 / c) * c >= 60) c1 = c;
+    return c1;
+  };
+  const int32_t nblk_full = (d_in + kBlockCols - 1) / kBlockCols;
+  g->nblk = nblk_full;
+  if (layout == OWQ_LAYOUT_COMPACT) {
+    // storage-favoured: only the columns that are not weak are stored (at least one block, of
+    // zeros), padded with zero columns up to the first block count that needs no more tiles per
+    // row tile than the full row: narrow tiles cost far more time than the blocks saved
+    const int32_t d_dense = d_in - k > 0 ? d_in - k : 1;
+    int32_t nb = (d_dense + kBlockCols - 1) / kBlockCols;
+    while (nb < nblk_full && nb / tile_width(nb) > nblk_full / tile_width(nblk_full)) ++nb;
+    g->nblk = nb;
+  }
+  const int cw = tile_width(g->nblk);
   g->cw = cw;
   g->r = 64 / cw;
   g->nact = g->r * cw;
@@ -84,6 +99,10 @@ owq_status_t compute_geometry(int32_t d_out, int32_t d_in, int32_t bits, int32_t
   g->off_weak_w = align_up(g->off_sz + (uint64_t)g->d_out_pad * g->n_groups * 4);
   g->off_weak_idx = align_up(g->off_weak_w + (uint64_t)g->d_out_pad * g->kp * 2);
   g->total_bytes = align_up(g->off_weak_idx + (uint64_t)g->kp * 4);
+  if (layout == OWQ_LAYOUT_COMPACT) {
+    g->off_wmask = g->total_bytes;        // per 8 input columns: weak mask | weak columns before << 8
+    g->total_bytes = align_up(g->off_wmask + (uint64_t)((d_in + 7) / 8) * 4);
+  }
   // The kernels address the blob with 32-bit byte offsets.
   if (g->total_bytes >= (1ull << 32)) return OWQ_ERR_SHAPE;
   return OWQ_OK;
@@ -180,15 +199,20 @@ void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *ou
     uint8_t *wm = out + g.off_wmask;
     for (int32_t j = 0; j < d->d_in; ++j)
       if (weak[j]) wm[j >> 3] |= (uint8_t)(1u << (j & 7));
-  } else
+  } else {
+  // stored column -> input column: all of them, or (storage-favoured) those that are not weak
+  std::vector<int32_t> col;
+  for (int32_t j = 0; j < d->d_in; ++j)
+    if (g.layout != OWQ_LAYOUT_COMPACT || !weak[j]) col.push_back(j);
+  const int32_t ncol = (int32_t)col.size();
   for (int32_t row = 0; row < g.d_out; ++row) {
     const int32_t rt = row / g.r, rloc = row % g.r;
     const uint8_t *src = d->codes + (int64_t)row * d->d_in;
     for (int32_t blk = 0; blk < g.nblk; ++blk) {
       const int32_t s = blk / g.cw, bloc = blk % g.cw;
       for (int c = 0; c < kBlockCols; ++c) {
-        const int32_t j = blk * kBlockCols + c;
-        q[c] = (j < d->d_in && !weak[j]) ? src[j] : 0;
+        const int32_t jc = blk * kBlockCols + c;
+        q[c] = (jc < ncol && !weak[col[jc]]) ? src[col[jc]] : 0;
       }
       block_to_dwords(q, g.bits, dw);
       const int64_t tile = (int64_t)rt * g.nslab + s;
@@ -198,6 +222,18 @@ void pack_blob(const owq_layer_desc_t *d, const owq_layer_info_t &g, uint8_t *ou
         codes[unit * 4 + (v & 3)] = dw[v];
       }
     }
+  }
+  if (g.layout == OWQ_LAYOUT_COMPACT) {
+    uint32_t *wm = reinterpret_cast<uint32_t *>(out + g.off_wmask);
+    uint32_t before = 0;
+    for (int32_t i = 0; i < (d->d_in + 7) / 8; ++i) {
+      uint32_t m = 0;
+      for (int e = 0; e < 8; ++e)
+        if (8 * i + e < d->d_in && weak[8 * i + e]) m |= 1u << e;
+      wm[i] = m | (before << 8);
+      before += (uint32_t)__builtin_popcount(m);
+    }
+  }
   }
 
   // single-token layout: [row][group]; tile layout: [group][row], so that the rows of a tile

@@ -79,6 +79,32 @@ def test_tile_layout_host_pack_equals_oracle_pack(lib, spec):
     assert _status(B.owq_packed_bytes, bad) == B.OWQ_ERR_LAYOUT
 
 
+@pytest.mark.parametrize("spec", [
+    LayerSpec("ca", 700, 45, 3, 0, 11, 21), LayerSpec("cb", 256, 32, 4, 0, 0, 22),
+    LayerSpec("cc", 1003, 70, 4, 0, 107, 23), LayerSpec("cd", 130, 3, 3, 0, 130, 24),
+    LayerSpec("ce", 128 * 6 + 8, 9, 3, 0, 8, 25)])
+def test_storage_favoured_layout_host_pack_equals_oracle_pack(lib, spec):
+    L = make_layer(spec)
+    d = B.desc_from_layer(L, B.OWQ_LAYOUT_COMPACT)
+    blob = B.owq_pack_host(d)
+    want, geo = packfmt.pack_layer(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, L.weak_w, L.bits,
+                                   layout=2)
+    info = B.owq_geometry(d)
+    for f in ("layout", "nblk", "cw", "r", "nact", "nslab", "n_rt", "d_out_pad", "chunks", "n_groups", "kp",
+              "off_codes", "off_sz", "off_weak_w", "off_weak_idx", "off_wmask", "total_bytes"):
+        assert getattr(info, f) == getattr(geo, f), f
+    np.testing.assert_array_equal(blob, want)
+    np.testing.assert_array_equal(B.owq_unpack_codes(blob, info), L.codes)
+    # fewer bytes than the full-size matrix whenever whole blocks of columns are saved
+    plain = B.owq_geometry(B.desc_from_layer(L, B.OWQ_LAYOUT_GEMV))
+    assert info.nblk <= plain.nblk
+
+
+def test_storage_favoured_layout_needs_one_scale_per_row(lib):
+    L = make_layer(LayerSpec("cg", 512, 8, 3, 128, 4, 9))
+    assert _status(B.owq_packed_bytes, B.desc_from_layer(L, B.OWQ_LAYOUT_COMPACT)) == B.OWQ_ERR_GROUP
+
+
 def _status(fn, *a):
     try:
         fn(*a)

@@ -168,3 +168,64 @@ def test_sz_dword_layout_by_hand():
     blob, geo = packfmt.pack_layer(codes, np.array([[1.0]], np.float16), np.array([[2.0]], np.float16),
                                    0, [], np.zeros((1, 0), np.float16), 4)
     assert blob[geo.off_sz:geo.off_sz + 4].tolist() == [0x00, 0x3C, 0x00, 0x40]
+
+
+# ---------------------------------------------------------------------------
+# storage-favoured layout (layout 2): the weak columns are not stored
+# ---------------------------------------------------------------------------
+
+def test_compact_layout_by_hand():
+    # 1 row, 136 columns, 8 of them weak: 128 stored columns = exactly one block
+    rng = np.random.default_rng(5)
+    codes = rng.integers(0, 8, size=(1, 136), dtype=np.uint8)
+    idx = np.array([0, 9, 10, 64, 127, 128, 130, 135], dtype=np.int32)
+    codes[:, idx] = 0
+    scale = np.array([[0.5]], dtype=np.float16)
+    zero = np.array([[3.0]], dtype=np.float16)
+    ww = rng.normal(size=(1, 8)).astype(np.float16)
+    blob, geo = packfmt.pack_layer(codes, scale, zero, 0, idx, ww, 3, layout=2)
+    assert (geo.layout, geo.nblk, geo.k, geo.kp) == (2, 1, 8, 8)
+    # the codes section is that of a 128-column layer holding the other columns in order
+    kept = np.delete(codes, idx, axis=1)
+    assert kept.shape == (1, 128)
+    plain, geo0 = packfmt.pack_layer(kept, scale, zero, 0, np.zeros(0, np.int32), np.zeros((1, 0), np.float16), 3)
+    assert geo.off_sz == geo0.off_sz
+    np.testing.assert_array_equal(blob[:geo.off_sz], plain[:geo0.off_sz])
+    # bookkeeping dwords, typed in by hand: unit i covers columns 8i .. 8i+7
+    meta = np.frombuffer(blob.tobytes(), dtype="<u4", count=17, offset=geo.off_wmask)
+    want_mask = {0: 0b00000001, 1: 0b00000110, 8: 0b00000001, 15: 0b10000000, 16: 0b10000101}
+    before = {0: 0, 1: 1, 2: 3, 8: 3, 9: 4, 15: 4, 16: 5}
+    count = 0
+    for i in range(17):
+        assert (meta[i] & 0xFF) == want_mask.get(i, 0), i
+        assert (meta[i] >> 8) == count, i
+        if i in before:
+            assert count == before[i]
+        count += bin(want_mask.get(i, 0)).count("1")
+    assert count == 8
+    np.testing.assert_array_equal(packfmt.unpack_codes(blob, geo), codes)
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+@pytest.mark.parametrize("d_out,d_in,k", [(5, 200, 7), (16, 256, 0), (9, 1000, 104), (3, 130, 130), (20, 128 * 9 + 5, 5)])
+def test_compact_layout_round_trip_and_size(bits, d_out, d_in, k):
+    L = make_layer(LayerSpec("c", d_in, d_out, bits, 0, k, 31 + k))
+    blob, geo = packfmt.pack_layer(L.codes, L.scale, L.zero, 0, L.weak_idx, L.weak_w, bits, layout=2)
+    plain = packfmt.geometry(d_out, d_in, bits, 0, k, 0)
+    stored = max(d_in - k, 1)
+    assert -(-stored // 128) <= geo.nblk <= plain.nblk and geo.nslab <= plain.nslab
+    # bytes of codes: rows (padded to whole tiles) x stored blocks x 16-byte chunks
+    assert geo.off_sz == -(-(geo.d_out_pad * geo.nblk * geo.chunks * 16) // 256) * 256
+    assert geo.nblk <= plain.nblk
+    assert blob.size == geo.total_bytes
+    np.testing.assert_array_equal(packfmt.unpack_codes(blob, geo), L.codes)
+    s, z, ix, ww = packfmt.unpack_params(blob, geo)
+    np.testing.assert_array_equal(ix, L.weak_idx)
+    np.testing.assert_array_equal(ww.view(np.uint16), L.weak_w.view(np.uint16))
+    np.testing.assert_array_equal(s.view(np.uint16), L.scale.view(np.uint16))
+
+
+def test_compact_layout_needs_one_scale_per_row():
+    L = make_layer(LayerSpec("c", 256, 8, 3, 128, 4, 1))
+    with pytest.raises(AssertionError):
+        packfmt.pack_layer(L.codes, L.scale, L.zero, 128, L.weak_idx, L.weak_w, 3, layout=2)
