@@ -27,10 +27,14 @@
 
 namespace owq {
 
+// What the kernel works with.  The launcher passes the packed form below: the kernel's
+// arguments then fit two 64-byte lines, and every further line a kernel reads at its start
+// costs about a quarter of a microsecond per launch here.
 struct GemvArgs {
   const u32x4 *codes;
   const u32 *sz;
   const u32x4 *weak_w;
+  // storage-favoured layout: not the indices but, per 8 input columns, weak mask | weak columns before << 8
   const int *weak_idx;
   const _Float16 *x;
   _Float16 *y;
@@ -41,14 +45,41 @@ struct GemvArgs {
   const void *const *weak_sets;
   const int *task_id;
   int n_sets;
-  // storage-favoured layout: per 8 input columns, weak mask | weak columns before << 8; d_dense = stored columns
-  const u32 *wmeta;
-  int d_dense;
-  int xper;   // 16-byte activation units per thread (ceil)
   // host-made reciprocals: n / d == (n * magic) >> 16 for the small n that occur (checked on the host)
   u32 cw_magic, nslab_magic, rsplit_magic, bpg_magic;
   int rtw, rsplit, items, xpitch, ppitch;
+  int nthr;     // threads per workgroup (from here, not from the launch's hidden arguments: one line less to read)
 };
+
+struct GemvPacked {                 // 128 bytes
+  const u32x4 *codes;
+  const u32 *sz;
+  const u32x4 *weak_w;
+  const int *weak_idx;
+  const _Float16 *x;
+  _Float16 *y;
+  const void *const *weak_sets;
+  const int *task_id;
+  int d_in, d_out, nblk, nslab, n_rt, n_groups, blocks_per_group, k, n_sets, xpitch;
+  u32 cw_r, rtw_rsplit;             // cw | r << 8 | waves per workgroup << 16; rtw | rsplit << 16
+  u32 cw_magic, nslab_magic, rsplit_magic, bpg_magic;
+
+  __device__ __forceinline__ GemvArgs unpack() const {
+    GemvArgs a;
+    a.codes = codes; a.sz = sz; a.weak_w = weak_w; a.weak_idx = weak_idx; a.x = x; a.y = y;
+    a.weak_sets = weak_sets; a.task_id = task_id; a.n_sets = n_sets;
+    a.d_in = d_in; a.d_out = d_out; a.nblk = nblk; a.nslab = nslab; a.n_rt = n_rt;
+    a.n_groups = n_groups; a.blocks_per_group = blocks_per_group;
+    a.cw = (int)(cw_r & 0xffu); a.r = (int)((cw_r >> 8) & 0xffu); a.nact = a.cw * a.r;
+    a.nthr = (int)(cw_r >> 16) * 64;
+    a.k = k; a.kp = (k + 7) & ~7; a.kchunks = a.kp >> 3;
+    a.rtw = (int)(rtw_rsplit & 0xffffu); a.rsplit = (int)(rtw_rsplit >> 16);
+    a.items = nslab * a.rsplit; a.xpitch = xpitch; a.ppitch = nblk;
+    a.cw_magic = cw_magic; a.nslab_magic = nslab_magic; a.rsplit_magic = rsplit_magic; a.bpg_magic = bpg_magic;
+    return a;
+  }
+};
+static_assert(sizeof(GemvPacked) == 128, "two lines of kernel arguments");
 
 // ---- 3-bit: 32 codes in three dwords --------------------------------------
 // Even columns form a 48-bit stream in the low halves of the three dwords, odd
@@ -165,7 +196,8 @@ __device__ long long g_trace[4096 * 16];
 // COMPACT: the layer stores only the columns that are not weak (storage-favoured layout): the
 // staging moves their activations together and drops the weak ones into their own array.
 template <int BITS, int DEPTH, bool HAS_WEAK, int XN, bool COMPACT = false>
-__global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const GemvArgs a) {
+__global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const GemvPacked packed) {
+  const GemvArgs a = packed.unpack();
   constexpr int CH = BITS == 3 ? 3 : 4;
   constexpr bool FAST = XN > 0;
   constexpr int XCH = FAST ? XN : 1;
@@ -177,7 +209,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   _Float16 *xw = reinterpret_cast<_Float16 *>(xw_u);
   float *part = reinterpret_cast<float *>(xw_u + xw_units);     // [rows of the workgroup][ppitch]
 
-  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int tid = threadIdx.x, nthr = a.nthr;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
   const _Float16 *xn = a.x + (size_t)blockIdx.y * a.d_in;
   _Float16 *yn = a.y + (size_t)blockIdx.y * a.d_out;
@@ -207,6 +239,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   // these does not wait for the weights behind them.  No branches: units past the
   // end re-read unit 0 and are dropped below, so that the number of loads in
   // flight is fixed and the waits can be exact.
+  const u32 *wmeta = reinterpret_cast<const u32 *>(a.weak_idx);     // COMPACT only
   uint4 xv[XCH];
   u32 wmv[XCH];
   int idx0 = -1;
@@ -216,7 +249,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
       const int i = tid + j * nthr;
       const int ic = (i * 8 < a.d_in) ? i : 0;
       xv[j] = *reinterpret_cast<const uint4 *>(xn + ic * 8);
-      if (COMPACT) wmv[j] = a.wmeta[ic];
+      if (COMPACT) wmv[j] = wmeta[ic];
     }
   }
   if (HAS_WEAK && !COMPACT) idx0 = a.weak_idx[tid < a.kp ? tid : 0];
@@ -306,7 +339,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
         *dst = h;
       }
     };
-    for (int c = a.d_dense + tid; c < a.nblk * 128; c += nthr) {      // past the last stored column
+    for (int c = a.d_in - a.k + tid; c < a.nblk * 128; c += nthr) {      // past the last stored column
       const int u = c >> 3;
       xs_h[((u & 15) * a.xpitch + (u >> 4)) * 8 + (c & 7)] = (_Float16)0;
     }
@@ -318,7 +351,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
         if (i * 8 < a.d_in) place(i, xv[j], wmv[j]);
       }
       for (int i = tid + XCH * nthr; i * 8 < a.d_in; i += nthr)         // very wide layers only
-        place(i, *reinterpret_cast<const uint4 *>(xn + i * 8), a.wmeta[i]);
+        place(i, *reinterpret_cast<const uint4 *>(xn + i * 8), wmeta[i]);
     } else {
       const bool vec = ((reinterpret_cast<uintptr_t>(xn) & 15) == 0) && ((a.d_in & 7) == 0);
       for (int i = tid; i * 8 < a.d_in; i += nthr) {
@@ -334,7 +367,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
           }
           v = *reinterpret_cast<const uint4 *>(e);
         }
-        place(i, v, a.wmeta[i]);
+        place(i, v, wmeta[i]);
       }
     }
   } else if (FAST) {
@@ -498,7 +531,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 // host side
 // ---------------------------------------------------------------------------
 
-typedef void (*kernel_fn)(const GemvArgs);
+typedef void (*kernel_fn)(const GemvPacked);
 
 template <int BITS, int DEPTH, bool WEAK, bool COMPACT>
 static kernel_fn pick3(int xn) {
@@ -551,7 +584,7 @@ int device_lds_limit(int32_t *bytes) {
 
 int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev, const TaskSets &tasks,
                 const void *x, void *y, int32_t batch, void *stream) {
-  GemvArgs a;
+  GemvPacked a;
   a.weak_sets = tasks.weak_sets; a.task_id = tasks.task_id; a.n_sets = tasks.n_sets;
   a.codes = static_cast<const u32x4 *>(dev.codes);
   a.sz = static_cast<const u32 *>(dev.sz);
@@ -559,25 +592,25 @@ int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLay
   a.weak_idx = static_cast<const int *>(dev.weak_idx);
   a.x = static_cast<const _Float16 *>(x);
   a.y = static_cast<_Float16 *>(y);
-  a.d_in = g.d_in; a.d_out = g.d_out; a.nblk = g.nblk; a.cw = g.cw; a.nact = g.nact;
-  a.nslab = g.nslab; a.n_rt = g.n_rt; a.r = g.r; a.n_groups = g.n_groups;
+  a.d_in = g.d_in; a.d_out = g.d_out; a.nblk = g.nblk; a.nslab = g.nslab; a.n_rt = g.n_rt;
+  a.n_groups = g.n_groups;
   a.blocks_per_group = g.group_size ? g.group_size / kBlockCols : 0;
-  a.k = g.k; a.kp = g.kp; a.kchunks = g.kp / 8;
-  a.rtw = s.rtw; a.rsplit = s.rsplit; a.items = g.nslab * s.rsplit;
+  a.k = g.k;
+  if (g.cw > 0xff || g.r > 0xff || s.rtw > 0xffff || s.rsplit > 0xffff) return (int)hipErrorInvalidValue;
+  a.cw_r = (u32)g.cw | ((u32)g.r << 8) | ((u32)s.waves << 16);
+  a.rtw_rsplit = (u32)s.rtw | ((u32)s.rsplit << 16);
   a.xpitch = s.xpitch;
-  a.ppitch = g.nblk;
   const int nthr = s.waves * 64;
   const bool compact = g.layout == OWQ_LAYOUT_COMPACT && g.kp > 0;
-  a.wmeta = static_cast<const u32 *>(dev.wmeta);
-  a.d_dense = g.d_in - g.k;
+  if (compact) a.weak_idx = static_cast<const int *>(dev.wmeta);
   // units a thread stages: the stored blocks, or (storage-favoured) the wider input row
   const int units = compact && (g.d_in + 7) / 8 > g.nblk * 16 ? (g.d_in + 7) / 8 : g.nblk * 16;
-  a.xper = (units + nthr - 1) / nthr;
+  const int xper = (units + nthr - 1) / nthr;
   a.cw_magic = s.cw_magic; a.nslab_magic = s.nslab_magic; a.rsplit_magic = s.rsplit_magic;
   a.bpg_magic = s.bpg_magic;
   // 16-byte staging from registers needs aligned rows
   const bool aligned = (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (g.d_in % 8 == 0);
-  const int xn = !aligned ? 0 : (a.xper <= 4 ? 4 : 8);
+  const int xn = !aligned ? 0 : (xper <= 4 ? 4 : 8);
   const dim3 grid((unsigned)s.nwg, (unsigned)batch, 1), block((unsigned)nthr, 1, 1);
   hipStream_t st = static_cast<hipStream_t>(stream);
   kernel_fn fn = pick(g.bits, s.depth, g.kp > 0, xn, compact);
