@@ -21,6 +21,11 @@ Pins (see tests marked "not gpu"):
                    packer, walking-ones patterns.
   bookkeeping      the closed forms and spot values of the paper's appendix D
                    and the memory row of the effective-bit sweep table.
+  search_config    (configuration search of s and z) weights exactly on a quantiser grid with
+                   and without an outlier that only a narrowed range absorbs, mirrored; weak
+                   columns that must not move anything; reported error against the pinned
+                   dequantiser; nested Python loops over the grid.  The grid itself is a
+                   reading (the paper leaves it open): see oracle/search.py.
   Numerics of y on the paper's real checkpoints: parity unpinned (the paper
   prints no output values and ships no weights).
 """
