@@ -236,6 +236,51 @@ owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes);
 owq_status_t owq_set_launch(owq_handle_t h, int32_t row_tiles_per_wg, int32_t row_splits,
                             int32_t waves_per_wg, int32_t prefetch_depth);
 
+/*
+ * Quantization configuration search (paper, section "Quantization Configuration Search"): for
+ * every output row and every group of its input columns, choose the step size and the zero
+ * point from a two-dimensional grid of narrowed ranges so that rounding to nearest with
+ * clamping changes the fp16 weights least.  The weak columns take no part: they are neither in
+ * the range nor in the error, and their codes are written as 0.  The outputs are what
+ * owq_layer_desc_t takes (after a copy to the host).
+ *
+ * The paper names the search and its objective; the grid is this library's reading.  With C the
+ * non-weak columns of the group, lo and hi the least and greatest weight over C, R = hi - lo:
+ *     grid       i in [0, n_lo), j in [0, n_hi):  lo_i = lo + a_i R,  hi_j = hi - b_j R,
+ *                a_i = shrink i / (n_lo - 1),  b_j = shrink j / (n_hi - 1)   (0 when n = 1)
+ *     candidate  s = fp16(max((hi_j - lo_i) / (2^bits - 1), 2^-14)),
+ *                z = clamp(rint(-lo_i (1 / s)), -2048, 2048)
+ *     codes      q = clamp(rint(w (1 / s)) + z, 0, 2^bits - 1)
+ *     error      E = sum over C of (w - s (q - z))^2
+ *     choice     least E; among equal E the least i n_hi + j
+ * R = 0: the range is widened to reach 0; still 0, or C empty: s = 1, z = 0, every code 0,
+ * E = 0, choice 0.  Every step that decides s, z or q is one IEEE binary32 operation (round
+ * half to even); E is summed in binary32, so that among candidates whose errors differ by less
+ * than that sum's rounding, either may be chosen.  Weights must be finite.
+ */
+typedef struct {
+  int32_t d_out, d_in;
+  int32_t bits;       /* 3 or 4 */
+  int32_t group_size; /* 0 = one group per row; else a multiple of 128 (the last group may be shorter) */
+  int32_t k;          /* number of weak columns, 0 <= k <= d_in */
+  int32_t n_lo, n_hi; /* grid points for the lower and the upper end of the range, 1..16 each */
+  float shrink;       /* largest fraction of R cut from one end, 0 <= shrink < 0.5 */
+} owq_search_desc_t;
+
+/*
+ * desc HOST.  DEVICE, owned by the caller, row-major: w fp16 bit patterns [d_out][d_in] (read);
+ * weak_idx [k] ascending column indices (read; may be NULL if k == 0; not checked: entries out
+ * of order or out of range give a wrong result, never an access out of bounds); written:
+ * scale, zero fp16 bit patterns [d_out][G], codes [d_out][d_in], and, unless NULL, err [d_out][G]
+ * (E of the choice) and choice [d_out][G] (i n_hi + j).  G = 1 if group_size == 0, else
+ * ceil(d_in / group_size).  One launch on `stream`, no allocation, no synchronisation.
+ * Errors: OWQ_ERR_NULL, OWQ_ERR_SHAPE (sizes below 1, d_out G above 2^31 - 1, grid or shrink out
+ * of range), OWQ_ERR_BITS, OWQ_ERR_GROUP, OWQ_ERR_INDEX (k out of range), OWQ_ERR_HIP.
+ */
+owq_status_t owq_search_config(const owq_search_desc_t *desc, const uint16_t *w, const int32_t *weak_idx,
+                               uint16_t *scale, uint16_t *zero, uint8_t *codes, float *err, int32_t *choice,
+                               void *stream);
+
 const char *owq_status_str(owq_status_t s);
 
 #ifdef __cplusplus

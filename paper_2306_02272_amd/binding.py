@@ -27,7 +27,8 @@ OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT = 0, 1, 2
 # every symbol include/owq.h declares
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
            "owq_open_packed", "owq_linear", "owq_free_layer", "owq_layer_info", "owq_export_packed", "owq_set_launch",
-           "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_status_str"]
+           "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_search_config",
+           "owq_status_str"]
 
 
 class OwqError(RuntimeError):
@@ -42,6 +43,11 @@ class LayerDesc(C.Structure):
                 ("group_size", C.c_int32), ("k", C.c_int32),
                 ("codes", C.c_void_p), ("scale", C.c_void_p), ("zero", C.c_void_p),
                 ("weak_idx", C.c_void_p), ("weak_w", C.c_void_p), ("layout", C.c_int32)]
+
+
+class SearchDesc(C.Structure):
+    _fields_ = [("d_out", C.c_int32), ("d_in", C.c_int32), ("bits", C.c_int32), ("group_size", C.c_int32),
+                ("k", C.c_int32), ("n_lo", C.c_int32), ("n_hi", C.c_int32), ("shrink", C.c_float)]
 
 
 class LayerInfo(C.Structure):
@@ -87,6 +93,7 @@ def lib():
         L.owq_weak_set_bytes.argtypes = [P, C.POINTER(SZ)]
         L.owq_pack_weak_set.argtypes = [P, P, P, SZ, P]
         L.owq_linear_multi.argtypes = [P, P, I32, P, P, P, I32, P]
+        L.owq_search_config.argtypes = [C.POINTER(SearchDesc), P, P, P, P, P, P, P, P]
         for n in EXPORTS:
             getattr(L, n).restype = C.c_int
         L.owq_status_str.argtypes = [C.c_int]
@@ -226,6 +233,37 @@ def owq_linear_multi(handle: int, weak_sets_ptr: int, n_sets: int, task_id_ptr: 
     _check(lib().owq_linear_multi(C.c_void_p(handle), C.c_void_p(weak_sets_ptr), n_sets, C.c_void_p(task_id_ptr),
                                   C.c_void_p(x_ptr), C.c_void_p(y_ptr), batch, C.c_void_p(stream)),
            "owq_linear_multi")
+
+
+def owq_search_config(desc: SearchDesc, w_ptr: int, weak_idx_ptr: int, scale_ptr: int, zero_ptr: int,
+                      codes_ptr: int, err_ptr: int = 0, choice_ptr: int = 0, stream: int = 0) -> None:
+    """Every pointer is a DEVICE address (0 = NULL where the header allows it)."""
+    _check(lib().owq_search_config(C.byref(desc), C.c_void_p(w_ptr), C.c_void_p(weak_idx_ptr), C.c_void_p(scale_ptr),
+                                   C.c_void_p(zero_ptr), C.c_void_p(codes_ptr), C.c_void_p(err_ptr),
+                                   C.c_void_p(choice_ptr), C.c_void_p(stream)), "owq_search_config")
+
+
+def search_config(w, weak_idx, bits, group_size, n_lo, n_hi, shrink, want_err=True):
+    """owq_search_config on CUDA tensors: w fp16 [d_out, d_in], weak_idx int32 [k] (or None).
+    Allocates the outputs with torch and returns (scale, zero, codes, err, choice) on the GPU."""
+    import torch
+    assert w.dtype == torch.float16 and w.is_cuda and w.is_contiguous() and w.dim() == 2
+    d_out, d_in = w.shape
+    k = 0 if weak_idx is None else int(weak_idx.numel())
+    if k:
+        assert weak_idx.dtype == torch.int32 and weak_idx.is_cuda and weak_idx.is_contiguous()
+    n_g = 1 if group_size == 0 or group_size >= d_in else -(-d_in // group_size)
+    dev = w.device
+    scale = torch.empty((d_out, n_g), dtype=torch.float16, device=dev)
+    zero = torch.empty((d_out, n_g), dtype=torch.float16, device=dev)
+    codes = torch.empty((d_out, d_in), dtype=torch.uint8, device=dev)
+    err = torch.empty((d_out, n_g), dtype=torch.float32, device=dev) if want_err else None
+    choice = torch.empty((d_out, n_g), dtype=torch.int32, device=dev) if want_err else None
+    desc = SearchDesc(d_out, d_in, bits, group_size, k, n_lo, n_hi, shrink)
+    owq_search_config(desc, w.data_ptr(), weak_idx.data_ptr() if k else 0, scale.data_ptr(), zero.data_ptr(),
+                      codes.data_ptr(), err.data_ptr() if want_err else 0, choice.data_ptr() if want_err else 0,
+                      torch.cuda.current_stream().cuda_stream)
+    return scale, zero, codes, err, choice
 
 
 def owq_status_str(status: int) -> str:

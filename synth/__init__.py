@@ -5,6 +5,6 @@ This module only draws random tensors and arranges them in the plain
 no packing, no dequantisation, no matrix product.  Both the CPU oracle's tests
 and the GPU library's tests and bench take their inputs from here.
 """
-from .layers import LayerSpec, Layer, make_layer, make_x, CONFIGS, config_layers
+from .layers import LayerSpec, Layer, make_layer, make_weights, make_x, CONFIGS, config_layers
 
-__all__ = ["LayerSpec", "Layer", "make_layer", "make_x", "CONFIGS", "config_layers"]
+__all__ = ["LayerSpec", "Layer", "make_layer", "make_weights", "make_x", "CONFIGS", "config_layers"]

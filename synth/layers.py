@@ -114,6 +114,32 @@ def make_layer(spec: LayerSpec, row_chunk: int = 2048) -> Layer:
     return Layer(spec, codes, scale, zero, weak_idx, weak_w)
 
 
+def make_weights(d_out: int, d_in: int, k: int, seed: int, weak_gain: float = 6.0,
+                 tail: float = 0.002, row_chunk: int = 2048):
+    """fp16 weights for the configuration search and the weak columns to leave out.
+
+    W ~ N(0, 0.02); a fraction `tail` of the entries is multiplied by U(3, 10) (the long tail
+    that a narrowed range cuts off); the k weak columns (top-k of lambda_i * |W_:,i|^2 with
+    lambda ~ LogNormal(0, 2), as for the layers) are multiplied by `weak_gain`: large values
+    that would dominate the range if they were not left out.  Returns (w [d_out, d_in] fp16,
+    weak_idx int32 [k] ascending)."""
+    rng = np.random.default_rng([seed, 7])
+    lam = rng.lognormal(mean=0.0, sigma=2.0, size=d_in)
+    w16 = np.empty((d_out, d_in), dtype=np.float16)
+    col_sq = np.zeros(d_in, dtype=np.float64)
+    for r0 in range(0, d_out, row_chunk):
+        r1 = min(d_out, r0 + row_chunk)
+        w = rng.normal(0.0, 0.02, size=(r1 - r0, d_in)).astype(np.float32)
+        big = rng.random(size=w.shape, dtype=np.float32) < tail
+        w = np.where(big, w * rng.uniform(3.0, 10.0, size=w.shape).astype(np.float32), w)
+        col_sq += np.einsum("ij,ij->j", w, w, dtype=np.float64)
+        w16[r0:r1] = w.astype(np.float16)
+    weak_idx = _top_k_columns(lam * col_sq, k)
+    if k:
+        w16[:, weak_idx] = (w16[:, weak_idx].astype(np.float32) * weak_gain).astype(np.float16)
+    return w16, weak_idx
+
+
 def make_x(layer: Layer, batch: int, seed: Optional[int] = None,
            mean: float = 0.0) -> np.ndarray:
     """fp16 activations [batch, d_in]; weak columns carry the outlier factor."""

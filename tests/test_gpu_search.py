@@ -1,0 +1,181 @@
+"""GPU parity of owq_search_config (configuration search of step size and zero point; paper,
+section "Quantization Configuration Search") against the CPU oracle, through the C ABI.
+
+What is compared.  Step size, zero point and codes are decided in binary32 on both sides and
+must agree bit for bit for the grid point the GPU chose.  The choice itself ranks sums that the
+kernel holds in binary32 and the oracle in binary64: where the two choices differ, the GPU's
+must be as good as the oracle's to within the rounding of the kernel's sum (RANK_TOL), and such
+cases must be rare.  The reported error must match the oracle's for that grid point (ERR_TOL).
+"""
+import numpy as np
+import pytest
+
+from oracle import search
+from synth import make_weights
+
+pytestmark = pytest.mark.gpu
+ERR_TOL = 1e-4       # relative, binary32 sum of up to 36864 squares against binary64
+RANK_TOL = 2e-4      # a differing choice may be worse than the best by this factor at most
+MAX_DIFFERING = 0.02 # fraction of (row, group) units whose choice may differ from the oracle's
+
+
+@pytest.fixture(scope="module")
+def env():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2306_02272_amd import binding
+    binding.lib()
+    torch.cuda.set_device(0)
+    return torch, binding
+
+
+def run_gpu(env, w, weak_idx, bits, gs, n_lo, n_hi, shrink):
+    torch, B = env
+    wd = torch.from_numpy(np.ascontiguousarray(w)).cuda()
+    idx = torch.from_numpy(np.ascontiguousarray(weak_idx, dtype=np.int32)).cuda() if len(weak_idx) else None
+    out = B.search_config(wd, idx, bits, gs, n_lo, n_hi, shrink)
+    torch.cuda.synchronize()
+    return [t.cpu().numpy() for t in out]
+
+
+def check_units(w, weak_idx, bits, gs, n_lo, n_hi, shrink, got, rows=None):
+    """Compare the GPU's outputs with the oracle for the given rows (all by default)."""
+    scale, zero, codes, err, choice = got
+    d_out, d_in = w.shape
+    g = d_in if gs == 0 or gs >= d_in else gs
+    n_g = -(-d_in // g)
+    assert scale.shape == zero.shape == err.shape == choice.shape == (d_out, n_g)
+    assert codes.shape == (d_out, d_in)
+    keep_all = np.ones(d_in, dtype=bool)
+    keep_all[np.asarray(weak_idx, dtype=np.int64)] = False
+    differing = units = 0
+    for r in (range(d_out) if rows is None else rows):
+        for gi in range(n_g):
+            c0, c1 = gi * g, min(d_in, (gi + 1) * g)
+            keep = keep_all[c0:c1]
+            where = (r, gi)
+            units += 1
+            s_ref, z_ref, q_ref, e_ref, ch_ref = search.search_group(w[r, c0:c1], keep, bits, n_lo, n_hi, shrink)
+            ch = int(choice[r, gi])
+            if ch != ch_ref:
+                # another grid point: must exist, and be as good to within the kernel's rounding
+                assert 0 <= ch < n_lo * n_hi, where
+                w32 = w[r, c0:c1].astype(np.float32)[keep]
+                pts = {p[0]: p for p in search.grid(w32, bits, n_lo, n_hi, shrink)}
+                _, s_ref, z_ref, q, e_alt = pts[ch]
+                assert e_alt <= e_ref * (1 + RANK_TOL) + 1e-30, (where, ch, ch_ref, e_alt, e_ref)
+                q_ref = np.zeros(c1 - c0, dtype=np.uint8)
+                q_ref[keep] = q.astype(np.uint8)
+                s_ref, z_ref, e_ref = np.float16(s_ref), np.float16(z_ref), e_alt
+                differing += 1
+            assert scale[r, gi].view(np.uint16) == np.float16(s_ref).view(np.uint16), where
+            assert zero[r, gi].view(np.uint16) == np.float16(z_ref).view(np.uint16), where
+            assert np.array_equal(codes[r, c0:c1], q_ref), where
+            assert err[r, gi] == pytest.approx(e_ref, rel=ERR_TOL, abs=1e-30), where
+    assert differing <= max(1, MAX_DIFFERING * units), (differing, units)
+
+
+CASES = [
+    # name, d_out, d_in, k, bits, group, n_lo, n_hi, shrink
+    ("g128_3bit_8x8", 40, 1024, 8, 3, 128, 8, 8, 0.3),
+    ("g128_4bit_10x12", 24, 768, 6, 4, 128, 10, 12, 0.25),         # two grid points per lane
+    ("g256_3bit_12x16", 16, 1024, 8, 3, 256, 12, 16, 0.4),          # three
+    ("row_3bit_16x16", 12, 2304, 16, 3, 0, 16, 16, 0.45),           # four; rows longer than one LDS pass
+    ("row_4bit_ragged", 9, 1000, 5, 4, 0, 6, 6, 0.3),               # d_in not a multiple of anything
+    ("g128_ragged_tail", 10, 1000, 5, 3, 128, 5, 7, 0.3),           # last group 104 columns
+    ("row_two_passes_exact", 6, 2048, 0, 4, 0, 4, 4, 0.2),          # no weak columns, two full passes
+    ("minmax_only", 20, 512, 4, 3, 128, 1, 1, 0.0),                 # 1 x 1 grid: plain min-max
+    ("lower_end_only", 10, 512, 4, 4, 128, 9, 1, 0.3),
+    ("upper_end_only", 10, 512, 4, 4, 128, 1, 9, 0.3),
+    ("g1152_long_groups", 5, 3456, 12, 3, 1152, 8, 8, 0.3),         # groups longer than one LDS pass
+    ("many_units", 700, 384, 3, 3, 128, 4, 4, 0.3),                 # more (row, group) units than one wave takes
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_search_matches_oracle(env, case):
+    name, d_out, d_in, k, bits, gs, n_lo, n_hi, shrink = case
+    w, idx = make_weights(d_out, d_in, k, seed=len(name) * 131 + d_in)
+    got = run_gpu(env, w, idx, bits, gs, n_lo, n_hi, shrink)
+    rows = None if d_out <= 64 else list(range(0, d_out, 37)) + [d_out - 1]
+    check_units(w, idx, bits, gs, n_lo, n_hi, shrink, got, rows)
+    assert not got[2][:, idx].any()
+
+
+def test_degenerate_rows_and_groups(env):
+    # all-zero row, constant rows of either sign, a group whose columns are all weak, a group with
+    # a single non-weak column, values at the ends of the fp16 range
+    d_in = 512
+    w, _ = make_weights(8, d_in, 0, seed=77)
+    w[0] = 0
+    w[1] = 1.5
+    w[2] = -0.375
+    w[3, :128] = 0
+    w[4, 200] = 60000.0
+    w[4, 201] = -60000.0
+    w[5] = (w[5].astype(np.float32) * 1e-4).astype(np.float16)      # denormal fp16 weights
+    idx = np.concatenate([np.arange(128, 256), np.arange(256, 383)]).astype(np.int32)   # group 1 all weak, group 2 one left
+    got = run_gpu(env, w, idx, 3, 128, 6, 6, 0.3)
+    check_units(w, idx, 3, 128, 6, 6, 0.3, got)
+    scale, zero, codes, err, choice = got
+    assert (scale[:, 1] == 1.0).all() and (zero[:, 1] == 0).all() and (err[:, 1] == 0).all()
+    assert not codes[:, 128:256].any() and not codes[0].any()
+    got = run_gpu(env, w, idx, 4, 0, 6, 6, 0.3)
+    check_units(w, idx, 4, 0, 6, 6, 0.3, got)
+
+
+def test_planted_grid_is_recovered(env):
+    # Weights exactly on a quantiser grid plus one outlier per row that only a narrowed range absorbs:
+    # the closed-form answer (s = 0.5, z = 0, E = 0.25), not just agreement with the oracle.
+    rng = np.random.default_rng(9)
+    q = rng.integers(0, 8, size=(32, 128))
+    q[:, :8] = np.arange(8)
+    w = (q * 0.5).astype(np.float16)
+    w[:, 8] = 4.0
+    scale, zero, codes, err, choice = run_gpu(env, w, [], 3, 0, 1, 3, 0.25)
+    q[:, 8] = 7
+    assert (scale == 0.5).all() and (zero == 0).all() and (choice == 1).all() and (err == 0.25).all()
+    assert np.array_equal(codes, q)
+
+
+def test_outputs_feed_the_layer(env):
+    # The search's outputs are a valid layer description: pack them and run the layer; the result is
+    # the product with the dequantised matrix the oracle builds from the same outputs.
+    from oracle import owq_ref
+    from synth import LayerSpec
+    from synth.layers import Layer
+    torch, B = env
+    d_out, d_in, k = 96, 1024, 8
+    w, idx = make_weights(d_out, d_in, k, seed=5)
+    scale, zero, codes, err, choice = run_gpu(env, w, idx, 3, 128, 8, 8, 0.3)
+    layer = Layer(LayerSpec("searched", d_in, d_out, 3, 128, k, 5), codes, scale, zero, idx,
+                  np.ascontiguousarray(w[:, idx]))
+    x = np.random.default_rng(6).normal(0, 1, size=(2, d_in)).astype(np.float16)
+    lin = B.OwqLinear(layer)
+    y = lin(torch.from_numpy(x).cuda()).cpu().numpy()
+    lin.close()
+    y_ref = owq_ref.owq_linear_ref(codes, scale, zero, 128, idx, w[:, idx], x)
+    rel, mx = owq_ref.parity_errors(y, y_ref)
+    assert rel <= 1e-3 and mx <= 1e-2
+    # and the searched layer is close to the fp16 one it came from
+    y_fp = x.astype(np.float64) @ w.astype(np.float64).T
+    assert np.linalg.norm(y_ref - y_fp) / np.linalg.norm(y_fp) < 0.25
+
+
+def test_full_size_sampled_rows(env):
+    # The shape the bench times (OPT-6.7B-like fc1: 16384 x 4096, 3-bit, groups of 128, 16 x 16 grid):
+    # sampled rows against the oracle.
+    w, idx = make_weights(16384, 4096, 32, seed=2000)
+    got = run_gpu(env, w, idx, 3, 128, 16, 16, 0.4)
+    check_units(w, idx, 3, 128, 16, 16, 0.4, got, rows=[0, 4097, 16383])
+    assert not got[2][:, idx].any()
+    assert got[2].max() <= 7
+
+
+def test_repeatable(env):
+    w, idx = make_weights(64, 1024, 8, seed=12)
+    a = run_gpu(env, w, idx, 4, 128, 8, 8, 0.3)
+    b = run_gpu(env, w, idx, 4, 128, 8, 8, 0.3)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)

@@ -184,3 +184,40 @@ def test_dead_handles_are_refused_by_the_weak_column_calls(lib):
     assert B.lib().owq_pack_weak_set(None, None, None, 0, None) == B.OWQ_ERR_HANDLE
     assert B.lib().owq_linear_multi(C.addressof(fake), None, 1, None, None, None, 1, None) == B.OWQ_ERR_HANDLE
     assert B.lib().owq_set_launch(None, 1, 1, 1, 2) == B.OWQ_ERR_HANDLE
+
+
+def test_search_rejects_bad_arguments(lib):
+    # Every check of owq_search_config comes before its launch, so the error paths need no GPU.
+    # The pointers are never dereferenced on these paths.
+    assert C.sizeof(B.SearchDesc) == 8 * 4
+    p = 256
+
+    def call(desc, w=p, idx=p, scale=p, zero=p, codes=p):
+        try:
+            B.owq_search_config(desc, w, idx, scale, zero, codes)
+        except B.OwqError as e:
+            return e.status
+        return B.OWQ_OK
+
+    good = dict(d_out=4, d_in=256, bits=3, group_size=128, k=2, n_lo=4, n_hi=4, shrink=0.3)
+
+    def desc(**kw):
+        f = dict(good, **kw)
+        return B.SearchDesc(f["d_out"], f["d_in"], f["bits"], f["group_size"], f["k"], f["n_lo"], f["n_hi"],
+                            f["shrink"])
+    assert call(desc(), w=0) == B.OWQ_ERR_NULL
+    assert call(desc(), codes=0) == B.OWQ_ERR_NULL
+    assert call(desc(), idx=0) == B.OWQ_ERR_NULL
+    assert call(desc(d_out=0)) == B.OWQ_ERR_SHAPE
+    assert call(desc(d_in=0)) == B.OWQ_ERR_SHAPE
+    assert call(desc(bits=5)) == B.OWQ_ERR_BITS
+    assert call(desc(group_size=100)) == B.OWQ_ERR_GROUP
+    assert call(desc(group_size=-128)) == B.OWQ_ERR_GROUP
+    assert call(desc(k=-1)) == B.OWQ_ERR_INDEX
+    assert call(desc(k=257)) == B.OWQ_ERR_INDEX
+    assert call(desc(n_lo=0)) == B.OWQ_ERR_SHAPE
+    assert call(desc(n_hi=17)) == B.OWQ_ERR_SHAPE
+    assert call(desc(shrink=0.5)) == B.OWQ_ERR_SHAPE
+    assert call(desc(shrink=-0.1)) == B.OWQ_ERR_SHAPE
+    assert call(desc(shrink=float("nan"))) == B.OWQ_ERR_SHAPE
+    assert call(desc(d_out=2 ** 31 - 1, d_in=2 ** 30, k=0)) == B.OWQ_ERR_SHAPE
