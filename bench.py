@@ -8,6 +8,11 @@ packed copies of the layers (distinct addresses, more than the 256 MB of
 last-level cache in total), as successive decoder blocks of a model would, so
 that the weights really come from HBM.
 
+The workloads named search-* time the other entry point, owq_search_config (the configuration
+search that produces a layer's step sizes, zero points and codes from fp16 weights): a step is one
+call over the whole matrix, the bound is the vector units (fp32 operations against the published
+fp32 vector peak).
+
 Prints ONE JSON line.  value = algorithmic bytes of a step / time of a step (GB/s);
 roofline.achieved = algorithmic bytes (or, on the tile layout, floating-point operations) per
 call / mean duration of a call from HIP events on the launch stream; roofline.traffic = HBM
@@ -52,12 +57,99 @@ def algorithmic_bytes(spec, batch: int, layout: int = 0) -> int:
             + index_bytes + 2 * batch * (spec.d_in + spec.d_out))
 
 
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+SEARCH_WORKLOADS = {
+    # name: (d_out, d_in, k, bits, group size, grid n_lo x n_hi, shrink, description)
+    "search-opt6.7b-fc1": (16384, 4096, 32, 3, 128, 16, 16, 0.4,
+                           "configuration search for an OPT-6.7B-like fc1 (16384 x 4096 fp16 weights, k=32 weak "
+                           "columns left out), 3-bit, group 128, 16 x 16 grid of narrowed ranges"),
+    "search-opt6.7b-fc1-row": (16384, 4096, 32, 3, 0, 16, 16, 0.4,
+                               "configuration search for an OPT-6.7B-like fc1 (16384 x 4096 fp16 weights, k=32 weak "
+                               "columns left out), 3-bit, one scale per row, 16 x 16 grid of narrowed ranges"),
+}
+SEARCH_FLOP = 7          # per weight and grid point: multiply, round, clamp, two fused multiply-adds
+
+
+def bench_search(args) -> int:
+    """A step = one owq_search_config call over the whole weight matrix, resident in HBM."""
+    import numpy as np
+    import torch
+
+    from paper_2306_02272_amd import binding as B
+    from synth import make_weights
+
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    d_out, d_in, k, bits, gs, n_lo, n_hi, shrink, desc = SEARCH_WORKLOADS[args.workload]
+    w_host, idx_host = make_weights(d_out, d_in, k, seed=2000)
+    w = torch.from_numpy(w_host).cuda()
+    idx = torch.from_numpy(idx_host).cuda()
+    n_g = 1 if gs == 0 else -(-d_in // gs)
+    scale = torch.empty((d_out, n_g), dtype=torch.float16, device="cuda")
+    zero = torch.empty_like(scale)
+    codes = torch.empty((d_out, d_in), dtype=torch.uint8, device="cuda")
+    err = torch.empty((d_out, n_g), dtype=torch.float32, device="cuda")
+    sd = B.SearchDesc(d_out, d_in, bits, gs, k, n_lo, n_hi, shrink)
+    stream = torch.cuda.Stream()
+    raw = stream.cuda_stream
+    steps, warmup = min(args.steps, 200), min(args.warmup, 20)
+
+    def run(n):
+        for _ in range(n):
+            B.owq_search_config(sd, w.data_ptr(), idx.data_ptr(), scale.data_ptr(), zero.data_ptr(), codes.data_ptr(),
+                                err.data_ptr(), 0, raw)
+
+    with torch.cuda.stream(stream):
+        run(warmup)
+        stream.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        run(steps)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    wall_s, event_s = t1 - t0, ev0.elapsed_time(ev1) * 1e-3
+    assert torch.isfinite(err).all() and int(codes.max()) <= (1 << bits) - 1
+    weights = d_out * (d_in - k)
+    flops = SEARCH_FLOP * weights * n_lo * n_hi
+    avg_launch_s = event_s / steps
+    tflops = flops / avg_launch_s / 1e12
+    result = {
+        "metric": f"configuration search, G weights/s ({n_lo} x {n_hi} grid points each), {bits}-bit",
+        "value": round(weights * steps / wall_s / 1e9, 3), "unit": "Gweights/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": round(wall_s / steps * 1e3, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": desc, "d_out": d_out, "d_in": d_in, "k": k, "group_size": gs, "grid": [n_lo, n_hi],
+                   "shrink": shrink, "launch_mode": "eager"},
+        "roofline": {"bound": "alu", "achieved": round(tflops, 1), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": f"owq_search_kernel<{-(-n_lo * n_hi // 64)}, {0 if gs == 0 or gs > 1024 else -(-gs // 64)}>",
+                     "avg_launch_us": round(avg_launch_s * 1e6, 1), "flops_per_launch": flops,
+                     "instructions_per_s": round(5 * weights * n_lo * n_hi / avg_launch_s / 1e12, 2)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import search
+        rows, c0 = 0, time.perf_counter()
+        while time.perf_counter() - c0 < 10.0:        # whole rows until about ten seconds have gone by
+            search.search_config(w_host[rows:rows + 1], idx_host, bits, gs, n_lo, n_hi, shrink)
+            rows += 1
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": round(rows * (d_in - k) / (c1 - c0) / 1e9, 9), "unit": "Gweights/s",
+                                  "cores": 1, "kind": "oracle",
+                                  "sample": f"the first {rows} of {d_out} rows, in {c1 - c0:.2f} s"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="opt6.7b-ffn", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="opt6.7b-ffn", choices=sorted(WORKLOADS) + sorted(SEARCH_WORKLOADS))
     ap.add_argument("--batch", type=int, default=0, help="tokens per call (default: the workload's own)")
     ap.add_argument("--layout", type=int, default=-1, help="0 = single-token layout, 1 = tile layout, 2 = storage-favoured single-token layout (default: the workload's own)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
@@ -75,6 +167,9 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         return 2
+
+    if args.workload in SEARCH_WORKLOADS:
+        return bench_search(args)
 
     import numpy as np
     import torch

@@ -129,9 +129,112 @@ __device__ __forceinline__ void accumulate(const Cand (&cd)[CPL], float (&e)[CPL
   }
 }
 
+// What the search of one (row, group) yields.
+struct Best {
+  float s, inv, z, e;
+  int id;
+};
+
+// The grid points of this lane for the range [lo, hi], errors cleared.
 template <int CPL>
+__device__ __forceinline__ void make_cands(float lo, float hi, const float (&fa)[CPL], const float (&fb)[CPL],
+                                           float qmax, Cand (&cd)[CPL], float (&e)[CPL]) {
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    cd[c] = candidate(lo, hi, fa[c], fb[c], qmax);
+    e[c] = 0.f;
+  }
+}
+
+// Adds the errors of list[0 .. cnt) to every grid point of this lane.
+template <int CPL>
+__device__ __forceinline__ void accumulate_list(const float *list, int cnt, const Cand (&cd)[CPL], float (&e)[CPL]) {
+  const f4v *l4 = reinterpret_cast<const f4v *>(list);
+  int i = 0;
+  f4v nxt = l4[0];                                 // one address for the wave: a broadcast
+  for (; i + 4 <= cnt; i += 4) {
+    const f4v v = nxt;
+    nxt = l4[(i >> 2) + 1];                        // one step ahead (the list has four spare entries)
+    accumulate<CPL>(cd, e, v[0]);
+    accumulate<CPL>(cd, e, v[1]);
+    accumulate<CPL>(cd, e, v[2]);
+    accumulate<CPL>(cd, e, v[3]);
+  }
+  for (; i < cnt; ++i) accumulate<CPL>(cd, e, list[i]);
+}
+
+// Ranks this lane's grid points, then the wave's; equal errors go to the lower index.  The
+// winner's step size and zero point are read from the lane that holds them.
+template <int CPL>
+__device__ __forceinline__ Best pick(const Cand (&cd)[CPL], const float (&e)[CPL], int ncand, int lane) {
+  float eb = INFINITY;
+  int ib = 0x7fffffff;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int id = lane + 64 * c;
+    if (id < ncand && (e[c] < eb || (e[c] == eb && id < ib))) {
+      eb = e[c];
+      ib = id;
+    }
+  }
+  const float e_min = wave_all(eb, [](float x, float y) { return x < y ? x : y; });
+  ib = wave_all(eb == e_min ? ib : 0x7fffffff, [](int x, int y) { return x < y ? x : y; });
+  ib = __builtin_amdgcn_readfirstlane(ib);
+  const int slot = ib >> 6, src = ib & 63;
+  auto from_lane = [&](float v) __attribute__((always_inline)) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src));
+  };
+  Best b;
+  b.s = from_lane(cd[0].s);
+  b.inv = from_lane(cd[0].inv);
+  float neg_z = from_lane(cd[0].a);
+#pragma unroll
+  for (int c = 1; c < CPL; ++c) {                  // slot is the same for the whole wave
+    const float s = from_lane(cd[c].s), inv = from_lane(cd[c].inv), na = from_lane(cd[c].a);
+    b.s = slot == c ? s : b.s;
+    b.inv = slot == c ? inv : b.inv;
+    neg_z = slot == c ? na : neg_z;
+  }
+  b.z = 0.f - neg_z;
+  b.e = e_min;
+  b.id = ib;
+  return b;
+}
+
+// Widens a zero-width range to reach 0; true if there is nothing to search.
+__device__ __forceinline__ bool degenerate(float &lo, float &hi, int kept) {
+  if (kept == 0) return true;
+  if (hi == lo) {
+    lo = lo < 0.f ? lo : 0.f;
+    hi = hi > 0.f ? hi : 0.f;
+    return hi == lo;
+  }
+  return false;
+}
+
+__device__ __forceinline__ void store_choice(const SearchArgs &a, int row, int gi, const Best &b, int lane) {
+  if (lane == 0) {
+    const size_t o = (size_t)row * a.n_groups + gi;
+    a.scale[o] = __builtin_bit_cast(uint16_t, (_Float16)b.s);
+    a.zero[o] = __builtin_bit_cast(uint16_t, (_Float16)b.z);
+    if (a.err != nullptr) a.err[o] = b.e;
+    if (a.choice != nullptr) a.choice[o] = b.id;
+  }
+}
+
+__device__ __forceinline__ uint8_t code_of(float v, const Best &b, float qmax) {
+  const float za = 0.f - b.z, zb = qmax - b.z;
+  return (uint8_t)(int)(__builtin_amdgcn_fmed3f(__builtin_rintf(v * b.inv), za, zb) - za);
+}
+
+// NT > 0: groups of at most 64 NT columns.  A lane keeps its NT weights of the group in
+// registers (they serve the range, the list in LDS and the codes), and the weights of the
+// wave's next group are fetched while the current one is searched.
+// NT = 0: longer groups, moved through LDS kChunk columns at a time, three passes over the row
+// (range, errors, codes).
+template <int CPL, int NT>
 __global__ __launch_bounds__(kWaves * 64) void owq_search_kernel(const SearchArgs a) {
-  __shared__ __attribute__((aligned(16))) float lists[kWaves][kChunk + 4];   // + 4: the loop reads one step ahead
+  __shared__ __attribute__((aligned(16))) float lists[kWaves][kChunk + 4];   // + 4: read one step ahead
   extern __shared__ u32 mask[];                    // bit c = column c is weak; (d_in + 31) / 32 words
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   float *list = lists[wv];
@@ -154,102 +257,134 @@ __global__ __launch_bounds__(kWaves * 64) void owq_search_kernel(const SearchArg
     fb[c] = cut_fraction(a.shrink, j, a.n_hi);
   }
   const int u0 = (blockIdx.x * kWaves + wv) * a.units_per_wave;
-  for (int uu = 0; uu < a.units_per_wave; ++uu) {
-    const int u = u0 + uu;
-    if (u >= a.units) break;                       // same for the whole wave
-    const int row = u / a.n_groups, gi = u - row * a.n_groups;
-    const int c0 = gi * a.g;
-    const int len = a.d_in - c0 < a.g ? a.d_in - c0 : a.g;
-    const _Float16 *wrow = a.w + (size_t)row * a.d_in;
-    const bool single = len <= kChunk;
-    // least and greatest non-weak weight
-    float lo = INFINITY, hi = -INFINITY;
-    int cnt = 0, kept = 0;
-    for (int o = 0; o < len; o += kChunk) {
-      cnt = stage(wrow, c0 + o, len - o < kChunk ? len - o : kChunk, list, mask, lane);
-      kept += cnt;
-      for (int e = lane; e < cnt; e += 64) {
-        const float v = list[e];
-        lo = v < lo ? v : lo;
-        hi = v > hi ? v : hi;
-      }
-    }
-    lo = wave_all(lo, [](float x, float y) { return x < y ? x : y; });
-    hi = wave_all(hi, [](float x, float y) { return x > y ? x : y; });
-    bool nothing = kept == 0;
-    if (!nothing && hi == lo) {
-      lo = lo < 0.f ? lo : 0.f;
-      hi = hi > 0.f ? hi : 0.f;
-      nothing = hi == lo;
-    }
-    float s_best = 1.f, z_best = 0.f, e_best = 0.f, inv_best = 1.f;
-    int id_best = 0;
-    if (!nothing) {
-      Cand cd[CPL];
-      float e[CPL];
+  const int n_units = a.units - u0 < a.units_per_wave ? a.units - u0 : a.units_per_wave;   // same for the wave
+  if (n_units <= 0) return;
+  int row = u0 / a.n_groups, gi = u0 - row * a.n_groups;
+  const Best none = {1.f, 1.f, 0.f, 0.f, 0};
+
+  if constexpr (NT > 0) {
+    // columns past the end of a short last group are fetched from its last column and dropped
+    auto fetch = [&](_Float16 (&dst)[NT], int r, int g) __attribute__((always_inline)) {
+      const int c0 = g * a.g;
+      const int last = (a.d_in - c0 < a.g ? a.d_in - c0 : a.g) - 1;
+      const _Float16 *src = a.w + (size_t)r * a.d_in + c0;
 #pragma unroll
-      for (int c = 0; c < CPL; ++c) {
-        cd[c] = candidate(lo, hi, fa[c], fb[c], a.qmax);
-        e[c] = 0.f;
+      for (int t = 0; t < NT; ++t) {
+        const int c = t * 64 + lane;
+        dst[t] = src[c < last ? c : last];
       }
+    };
+    _Float16 cur[NT], nxt[NT];
+    fetch(cur, row, gi);
+    for (int uu = 0; uu < n_units; ++uu) {
+      const int c0 = gi * a.g;
+      const int len = a.d_in - c0 < a.g ? a.d_in - c0 : a.g;
+      int nrow = row, ngi = gi + 1;
+      if (ngi == a.n_groups) {
+        ngi = 0;
+        ++nrow;
+      }
+      if (uu + 1 < n_units) fetch(nxt, nrow, ngi);
+      // range and list straight from the registers
+      float lo = INFINITY, hi = -INFINITY;
+      int cnt = 0;
+      u32 weak_bits = 0u;                          // bit t: slot t of this lane is no weight of the search
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int c = t * 64 + lane;
+        const bool keep = c < len && !is_weak(mask, c0 + (c < len ? c : 0));
+        const float v = (float)cur[t];
+        const unsigned long long m = __ballot(keep);
+        const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, 0u));
+        if (keep) {
+          list[pos] = v;
+          lo = v < lo ? v : lo;
+          hi = v > hi ? v : hi;
+        } else {
+          weak_bits |= 1u << t;
+        }
+        cnt += __builtin_popcountll(m);
+      }
+      wave_lds_fence();
+      lo = wave_all(lo, [](float x, float y) { return x < y ? x : y; });
+      hi = wave_all(hi, [](float x, float y) { return x > y ? x : y; });
+      const bool nothing = degenerate(lo, hi, cnt);
+      Best best = none;
+      if (!nothing) {
+        Cand cd[CPL];
+        float e[CPL];
+        make_cands<CPL>(lo, hi, fa, fb, a.qmax, cd, e);
+        accumulate_list<CPL>(list, cnt, cd, e);
+        best = pick<CPL>(cd, e, ncand, lane);
+      }
+      wave_lds_fence();                            // the list is rewritten for the next group
+      store_choice(a, row, gi, best, lane);
+      uint8_t *crow = a.codes + (size_t)row * a.d_in + c0;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int c = t * 64 + lane;
+        const uint8_t q = (nothing || ((weak_bits >> t) & 1u)) ? (uint8_t)0 : code_of((float)cur[t], best, a.qmax);
+        if (c < len) crow[c] = q;
+      }
+#pragma unroll
+      for (int t = 0; t < NT; ++t) cur[t] = nxt[t];
+      row = nrow;
+      gi = ngi;
+    }
+  } else {
+    for (int uu = 0; uu < n_units; ++uu) {
+      const int c0 = gi * a.g;
+      const int len = a.d_in - c0 < a.g ? a.d_in - c0 : a.g;
+      const _Float16 *wrow = a.w + (size_t)row * a.d_in;
+      // least and greatest non-weak weight
+      float lo = INFINITY, hi = -INFINITY;
+      int kept = 0;
       for (int o = 0; o < len; o += kChunk) {
-        if (!single) cnt = stage(wrow, c0 + o, len - o < kChunk ? len - o : kChunk, list, mask, lane);
-        const f4v *l4 = reinterpret_cast<const f4v *>(list);
-        int i = 0;
-        f4v nxt = l4[0];                           // one address for the wave: a broadcast
-        for (; i + 4 <= cnt; i += 4) {
-          const f4v v = nxt;
-          nxt = l4[(i >> 2) + 1];
-          accumulate<CPL>(cd, e, v[0]);
-          accumulate<CPL>(cd, e, v[1]);
-          accumulate<CPL>(cd, e, v[2]);
-          accumulate<CPL>(cd, e, v[3]);
+        const int cnt = stage(wrow, c0 + o, len - o < kChunk ? len - o : kChunk, list, mask, lane);
+        kept += cnt;
+        for (int e = lane; e < cnt; e += 64) {
+          const float v = list[e];
+          lo = v < lo ? v : lo;
+          hi = v > hi ? v : hi;
         }
-        for (; i < cnt; ++i) accumulate<CPL>(cd, e, list[i]);
-        if (!single) wave_lds_fence();             // the list is rewritten by the next chunk
+        wave_lds_fence();
       }
-      // rank: this lane's grid points, then the wave's; equal errors go to the lower index
-      float eb = INFINITY;
-      int ib = 0x7fffffff;
-#pragma unroll
-      for (int c = 0; c < CPL; ++c) {
-        const int id = lane + 64 * c;
-        if (id < ncand && (e[c] < eb || (e[c] == eb && id < ib))) {
-          eb = e[c];
-          ib = id;
+      lo = wave_all(lo, [](float x, float y) { return x < y ? x : y; });
+      hi = wave_all(hi, [](float x, float y) { return x > y ? x : y; });
+      const bool nothing = degenerate(lo, hi, kept);
+      Best best = none;
+      if (!nothing) {
+        Cand cd[CPL];
+        float e[CPL];
+        make_cands<CPL>(lo, hi, fa, fb, a.qmax, cd, e);
+        for (int o = 0; o < len; o += kChunk) {
+          const int cnt = stage(wrow, c0 + o, len - o < kChunk ? len - o : kChunk, list, mask, lane);
+          accumulate_list<CPL>(list, cnt, cd, e);
+          wave_lds_fence();                        // the list is rewritten by the next pass
         }
+        best = pick<CPL>(cd, e, ncand, lane);
       }
-      const float e_min = wave_all(eb, [](float x, float y) { return x < y ? x : y; });
-      ib = wave_all(eb == e_min ? ib : 0x7fffffff, [](int x, int y) { return x < y ? x : y; });
-      eb = e_min;
-      const int i = ib / a.n_hi, j = ib - i * a.n_hi;
-      const Cand best = candidate(lo, hi, cut_fraction(a.shrink, i, a.n_lo), cut_fraction(a.shrink, j, a.n_hi), a.qmax);
-      s_best = best.s;
-      inv_best = best.inv;
-      z_best = 0.f - best.a;
-      e_best = eb;
-      id_best = ib;
-    }
-    if (lane == 0) {
-      const size_t o = (size_t)row * a.n_groups + gi;
-      a.scale[o] = __builtin_bit_cast(uint16_t, (_Float16)s_best);
-      a.zero[o] = __builtin_bit_cast(uint16_t, (_Float16)z_best);
-      if (a.err != nullptr) a.err[o] = e_best;
-      if (a.choice != nullptr) a.choice[o] = id_best;
-    }
-    // the codes of the group under the chosen step size and zero point; 0 at weak columns
-    uint8_t *crow = a.codes + (size_t)row * a.d_in;
-    const float za = 0.f - z_best, zb = a.qmax - z_best;
-    for (int o = 0; o < len; o += kChunk) {
-      const int n = len - o < kChunk ? len - o : kChunk;
-      for (int c = lane; c < n; c += 64) {
-        const float v = (float)wrow[c0 + o + c];
-        const float t = v * inv_best;
-        const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), za, zb) - za;
-        crow[c0 + o + c] = (nothing || is_weak(mask, c0 + o + c)) ? (uint8_t)0 : (uint8_t)(int)q;
+      store_choice(a, row, gi, best, lane);
+      // the codes of the group under the chosen step size and zero point; 0 at weak columns
+      uint8_t *crow = a.codes + (size_t)row * a.d_in;
+      for (int c = c0 + lane; c < c0 + len; c += 64)
+        crow[c] = (nothing || is_weak(mask, c)) ? (uint8_t)0 : code_of((float)wrow[c], best, a.qmax);
+      if (++gi == a.n_groups) {
+        gi = 0;
+        ++row;
       }
     }
   }
+}
+
+typedef void (*search_fn)(const SearchArgs);
+template <int CPL>
+search_fn pick_nt(int g) {
+  if (g <= 128) return owq_search_kernel<CPL, 2>;
+  if (g <= 256) return owq_search_kernel<CPL, 4>;
+  if (g <= 512) return owq_search_kernel<CPL, 8>;
+  if (g <= kChunk) return owq_search_kernel<CPL, 16>;
+  return owq_search_kernel<CPL, 0>;
 }
 
 }  // namespace
@@ -298,9 +433,7 @@ extern "C" owq_status_t owq_search_config(const owq_search_desc_t *d, const uint
   const dim3 grid((unsigned)((waves + kWaves - 1) / kWaves)), block(kWaves * 64);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int ncand = d->n_lo * d->n_hi;
-  if (ncand <= 64) hipLaunchKernelGGL(owq_search_kernel<1>, grid, block, mask_bytes, st, a);
-  else if (ncand <= 128) hipLaunchKernelGGL(owq_search_kernel<2>, grid, block, mask_bytes, st, a);
-  else if (ncand <= 192) hipLaunchKernelGGL(owq_search_kernel<3>, grid, block, mask_bytes, st, a);
-  else hipLaunchKernelGGL(owq_search_kernel<4>, grid, block, mask_bytes, st, a);
+  const search_fn fn = ncand <= 64 ? pick_nt<1>(g) : ncand <= 128 ? pick_nt<2>(g) : ncand <= 192 ? pick_nt<3>(g) : pick_nt<4>(g);
+  hipLaunchKernelGGL(fn, grid, block, mask_bytes, st, a);
   return hipGetLastError() == hipSuccess ? OWQ_OK : OWQ_ERR_HIP;
 }

@@ -89,6 +89,9 @@ CASES = [
     ("lower_end_only", 10, 512, 4, 4, 128, 9, 1, 0.3),
     ("upper_end_only", 10, 512, 4, 4, 128, 1, 9, 0.3),
     ("g1152_long_groups", 5, 3456, 12, 3, 1152, 8, 8, 0.3),         # groups longer than one LDS pass
+    ("g512_4bit", 8, 1536, 6, 4, 512, 8, 8, 0.3),
+    ("g384_3bit_ragged_tail", 8, 1000, 6, 3, 384, 7, 9, 0.3),       # 384 + 384 + 232
+    ("g640_3bit", 6, 1920, 6, 3, 640, 8, 16, 0.3),
     ("many_units", 700, 384, 3, 3, 128, 4, 4, 0.3),                 # more (row, group) units than one wave takes
 ]
 
