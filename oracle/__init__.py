@@ -26,6 +26,9 @@ Pins (see tests marked "not gpu"):
                    columns that must not move anything; reported error against the pinned
                    dequantiser; nested Python loops over the grid.  The grid itself is a
                    reading (the paper leaves it open): see oracle/search.py.
+  owq_backward_ref (derivatives for weak-column tuning) the adjoint identities against the pinned
+                   forward oracle, unit-vector responses entry by entry, central differences
+                   of the forward loops, all columns weak, nested loops.
   Numerics of y on the paper's real checkpoints: parity unpinned (the paper
   prints no output values and ships no weights).
 """
