@@ -281,6 +281,32 @@ owq_status_t owq_search_config(const owq_search_desc_t *desc, const uint16_t *w,
                                uint16_t *scale, uint16_t *zero, uint8_t *codes, float *err, int32_t *choice,
                                void *stream);
 
+/*
+ * Backward of the layer for weak-column tuning (paper, section "PEFT with Weak Column Tuning":
+ * after quantisation only the fp16 weak columns are trained, the low-bit matrix stays as it
+ * is).  The layer is linear, so its derivatives are its transposes.  With dy = dL/dy:
+ *
+ *     dx[n, j]            = sum_i dy[n, i] s[i, g(j)] (q[i, j] - z[i, g(j)])      j not weak
+ *     dx[n, weak_idx[t]]  = sum_i dy[n, i] Ww[i, t]
+ *     dww[i, t]           = sum_n dy[n, i] x[n, weak_idx[t]]
+ *
+ * Handles of OWQ_LAYOUT_TILE only (else OWQ_ERR_LAYOUT): the codes go from the packed tiles
+ * through the matrix cores twice, once to turn them (rows into the contraction axis), once for
+ * the product.  DEVICE pointers, owned by the caller, row-major, 16-byte aligned: dy fp16
+ * [batch][d_out] (read), x fp16 [batch][d_in] (read; only its weak columns; may be NULL if dww
+ * is NULL), dx fp16 [batch][d_in] (written; NULL = not wanted), dww fp32 [d_out][k] (written,
+ * summed over the whole batch; NULL = not wanted), workspace of at least
+ * owq_backward_workspace_bytes bytes, 256-byte aligned (contents undefined before and after;
+ * calls that share a workspace must not overlap).  fp32 accumulation; dy times the step size is
+ * rounded to fp16 once before the product (relative 2^-11 per term); dx is rounded to fp16
+ * once.  Work is queued on `stream`, nothing is allocated, nothing synchronises.
+ * Errors: OWQ_ERR_HANDLE, OWQ_ERR_LAYOUT, OWQ_ERR_NULL, OWQ_ERR_BATCH, OWQ_ERR_BUFFER (workspace
+ * too small, a pointer misaligned), OWQ_ERR_HIP.  batch == 0 is a no-op.
+ */
+owq_status_t owq_backward_workspace_bytes(owq_handle_t h, int32_t batch, size_t *bytes);
+owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, const void *x, void *dx, float *dww,
+                                 int32_t batch, void *workspace, size_t workspace_bytes, void *stream);
+
 const char *owq_status_str(owq_status_t s);
 
 #ifdef __cplusplus

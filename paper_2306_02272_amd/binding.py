@@ -28,6 +28,7 @@ OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT = 0, 1, 2
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
            "owq_open_packed", "owq_linear", "owq_free_layer", "owq_layer_info", "owq_export_packed", "owq_set_launch",
            "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_search_config",
+           "owq_backward_workspace_bytes", "owq_linear_backward",
            "owq_status_str"]
 
 
@@ -94,6 +95,8 @@ def lib():
         L.owq_pack_weak_set.argtypes = [P, P, P, SZ, P]
         L.owq_linear_multi.argtypes = [P, P, I32, P, P, P, I32, P]
         L.owq_search_config.argtypes = [C.POINTER(SearchDesc), P, P, P, P, P, P, P, P]
+        L.owq_backward_workspace_bytes.argtypes = [P, I32, C.POINTER(SZ)]
+        L.owq_linear_backward.argtypes = [P, P, P, P, P, I32, P, SZ, P]
         for n in EXPORTS:
             getattr(L, n).restype = C.c_int
         L.owq_status_str.argtypes = [C.c_int]
@@ -266,6 +269,20 @@ def search_config(w, weak_idx, bits, group_size, n_lo, n_hi, shrink, want_err=Tr
     return scale, zero, codes, err, choice
 
 
+def owq_backward_workspace_bytes(handle: int, batch: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().owq_backward_workspace_bytes(C.c_void_p(handle), batch, C.byref(n)), "owq_backward_workspace_bytes")
+    return int(n.value)
+
+
+def owq_linear_backward(handle: int, dy_ptr: int, x_ptr: int, dx_ptr: int, dww_ptr: int, batch: int,
+                        workspace_ptr: int, workspace_bytes: int, stream: int = 0) -> None:
+    """Every pointer is a DEVICE address (0 = NULL where the header allows it)."""
+    _check(lib().owq_linear_backward(C.c_void_p(handle), C.c_void_p(dy_ptr), C.c_void_p(x_ptr), C.c_void_p(dx_ptr),
+                                     C.c_void_p(dww_ptr), batch, C.c_void_p(workspace_ptr), workspace_bytes,
+                                     C.c_void_p(stream)), "owq_linear_backward")
+
+
 def owq_status_str(status: int) -> str:
     return lib().owq_status_str(status).decode()
 
@@ -328,6 +345,25 @@ class OwqLinear:
         owq_linear_multi(self.handle, table.data_ptr(), int(table.numel()), task_id.data_ptr(), x.data_ptr(),
                          out.data_ptr(), batch, torch.cuda.current_stream().cuda_stream)
         return out
+
+    def backward(self, dy, x=None, want_dx=True, want_dww=True, workspace=None):
+        """owq_linear_backward on CUDA tensors; returns (dx fp16 [batch, d_in] or None, dww fp32 [d_out, k] or None)."""
+        torch = self.torch
+        assert dy.dtype == torch.float16 and dy.is_cuda and dy.is_contiguous() and dy.shape[-1] == self.d_out
+        batch = dy.numel() // self.d_out
+        k = self.desc.k
+        dx = torch.empty((batch, self.d_in), dtype=torch.float16, device=dy.device) if want_dx else None
+        dww = torch.empty((self.d_out, k), dtype=torch.float32, device=dy.device) if want_dww else None
+        if want_dww and k > 0:
+            assert x is not None and x.dtype == torch.float16 and x.is_contiguous() and x.numel() == batch * self.d_in
+        if workspace is None and want_dx:
+            workspace = torch.empty(owq_backward_workspace_bytes(self.handle, batch), dtype=torch.uint8, device=dy.device)
+        owq_linear_backward(self.handle, dy.data_ptr(), x.data_ptr() if x is not None else 0,
+                            dx.data_ptr() if want_dx else 0, dww.data_ptr() if (want_dww and k > 0) else 0, batch,
+                            workspace.data_ptr() if workspace is not None else 0,
+                            int(workspace.numel()) if workspace is not None else 0,
+                            torch.cuda.current_stream().cuda_stream)
+        return dx, dww
 
     def close(self):
         if self.handle:

@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["owq_api.cpp", "owq_pack.cpp", "owq_kernels.hip", "owq_tile.hip", "owq_tile_small.hip", "owq_search.hip"]
+SOURCES = ["owq_api.cpp", "owq_pack.cpp", "owq_kernels.hip", "owq_tile.hip", "owq_tile_small.hip", "owq_search.hip", "owq_backward.hip"]
 LIB = os.path.join(HERE, "libowq.so")
 
 
