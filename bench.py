@@ -144,12 +144,108 @@ def bench_search(args) -> int:
     return 0
 
 
+BACKWARD_WORKLOADS = {
+    # name: (index in the list of benchmark configurations, layer indices, tokens, description)
+    "backward-opt6.7b-ffn": (2, [0, 1], 512, "backward (dX and dWw, weak-column tuning) of configs[2]'s OPT-6.7B-like FFN "
+                                             "pair, 3-bit, group 128, 512 tokens, tile layout"),
+}
+
+
+def bench_backward(args) -> int:
+    """A step = owq_linear_backward (dX and dWw) of every layer of the workload for one batch of tokens."""
+    import numpy as np
+    import torch
+
+    from paper_2306_02272_amd import binding as B
+    from synth import CONFIGS, make_layer, make_x
+
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg, layer_ids, batch, desc = BACKWARD_WORKLOADS[args.workload]
+    if args.batch:
+        batch = args.batch
+    specs = [CONFIGS[cfg][i] for i in layer_ids]
+    layers = [make_layer(s) for s in specs]
+    lins = [B.OwqLinear(L, layout=1) for L in layers]
+    rng = np.random.default_rng(5)
+    xs_host = [make_x(L, batch) for L in layers]
+    dys_host = [rng.normal(0, 0.05, size=(batch, L.d_out)).astype(np.float16) for L in layers]
+    xs = [torch.from_numpy(x).cuda() for x in xs_host]
+    dys = [torch.from_numpy(d).cuda() for d in dys_host]
+    dxs = [torch.empty((batch, L.d_in), dtype=torch.float16, device="cuda") for L in layers]
+    dwws = [torch.empty((L.d_out, L.k), dtype=torch.float32, device="cuda") for L in layers]
+    wss = [torch.empty(B.owq_backward_workspace_bytes(lin.handle, batch), dtype=torch.uint8, device="cuda") for lin in lins]
+    stream = torch.cuda.Stream()
+    raw = stream.cuda_stream
+    steps, warmup = min(args.steps, 200), min(args.warmup, 20)
+
+    def run(n):
+        for _ in range(n):
+            for lin, x, dy, dx, dww, ws in zip(lins, xs, dys, dxs, dwws, wss):
+                B.owq_linear_backward(lin.handle, dy.data_ptr(), x.data_ptr(), dx.data_ptr(), dww.data_ptr(), batch,
+                                      ws.data_ptr(), int(ws.numel()), raw)
+
+    with torch.cuda.stream(stream):
+        run(warmup)
+        stream.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        run(steps)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    wall_s, event_s = t1 - t0, ev0.elapsed_time(ev1) * 1e-3
+    for dx in dxs:
+        assert torch.isfinite(dx).all()
+    # dense product + the two weak-column products
+    flops_step = sum(2 * batch * sp.d_out * sp.d_in + 4 * batch * sp.d_out * sp.k for sp in specs)
+    calls = steps * len(specs)
+    avg_call_s = event_s / calls
+    tflops = flops_step / len(specs) / avg_call_s / 1e12
+    result = {
+        "metric": f"backward of the {specs[0].bits}-bit OWQ linear (dX, dWw), tokens/s, {batch} tokens",
+        "value": round(batch * steps / wall_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(wall_s / steps * 1e3, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 operands (dy x step size rounded to f16), f32 accumulate", "data": "synthetic",
+        "config": {"workload": desc, "batch": batch, "layers": [s.name for s in specs], "launch_mode": "eager"},
+        "us_per_call": round(wall_s / calls * 1e6, 3),
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": f"owq_bwd_product<{specs[0].bits}> (+ stage, sum, weak, dww)",
+                     "avg_launch_us": round(avg_call_s * 1e6, 3), "flops_per_launch": flops_step // len(specs)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import backward
+        # a bounded sample: the first tokens of the batch and the first rows of every layer
+        nt, c0, reps = min(batch, 8), time.perf_counter(), 0
+        while True:
+            for L, x, dy in zip(layers, xs_host, dys_host):
+                rows = max(1, L.d_out // 8)
+                backward.owq_backward_ref(L.codes[:rows], L.scale[:rows], L.zero[:rows], L.group_size, L.weak_idx,
+                                          L.weak_w[:rows], x[:nt], dy[:nt, :rows])
+            reps += 1
+            if time.perf_counter() - c0 >= 10.0:
+                break
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": round(reps * nt / 8 / (c1 - c0), 3), "unit": "tokens/s", "cores": 1,
+                                  "kind": "oracle",
+                                  "sample": f"{reps} x ({nt} tokens, the first eighth of the output rows of each layer) "
+                                            f"in {c1 - c0:.2f} s"}
+    print(json.dumps(result), flush=True)
+    for lin in lins:
+        lin.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="opt6.7b-ffn", choices=sorted(WORKLOADS) + sorted(SEARCH_WORKLOADS))
+    ap.add_argument("--workload", default="opt6.7b-ffn", choices=sorted(WORKLOADS) + sorted(SEARCH_WORKLOADS) + sorted(BACKWARD_WORKLOADS))
     ap.add_argument("--batch", type=int, default=0, help="tokens per call (default: the workload's own)")
     ap.add_argument("--layout", type=int, default=-1, help="0 = single-token layout, 1 = tile layout, 2 = storage-favoured single-token layout (default: the workload's own)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
@@ -170,6 +266,8 @@ def main() -> int:
 
     if args.workload in SEARCH_WORKLOADS:
         return bench_search(args)
+    if args.workload in BACKWARD_WORKLOADS:
+        return bench_backward(args)
 
     import numpy as np
     import torch

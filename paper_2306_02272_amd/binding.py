@@ -356,7 +356,7 @@ class OwqLinear:
         dww = torch.empty((self.d_out, k), dtype=torch.float32, device=dy.device) if want_dww else None
         if want_dww and k > 0:
             assert x is not None and x.dtype == torch.float16 and x.is_contiguous() and x.numel() == batch * self.d_in
-        if workspace is None and want_dx:
+        if workspace is None:
             workspace = torch.empty(owq_backward_workspace_bytes(self.handle, batch), dtype=torch.uint8, device=dy.device)
         owq_linear_backward(self.handle, dy.data_ptr(), x.data_ptr() if x is not None else 0,
                             dx.data_ptr() if want_dx else 0, dww.data_ptr() if (want_dww and k > 0) else 0, batch,

@@ -16,9 +16,12 @@
 // No LDS and no shuffles are needed for the turn.  The zero-point term sum_i a[n, i] z[i] is
 // summed on the vector units beside the matrix instructions and taken off at the end.
 //
-// Four launches per pass of up to 128 tokens (stage dy, product into fp32 partial results per
-// range of rows, sum of the partial results into fp16 dx, the weak columns of dx), one more
-// for dww over the whole batch.
+// Three launches per pass of up to 128 tokens (stage dy; product into fp32 partial results per
+// range of rows, the weak columns of dx riding along as one more tile of columns per workgroup;
+// sum of the partial results into fp16 dx), one before them that puts the weak columns in
+// operand order, two more for dww over the whole batch (the activations at the weak columns into
+// operand order, then a product with the tokens on the contraction axis).  A layer with more tiles of weak
+// columns than block pairs takes a plain kernel for the weak columns of dx instead.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -60,15 +63,43 @@ __global__ __launch_bounds__(256) void owq_bwd_stage(const StageArgs a) {
   a.a_st[u] = __builtin_bit_cast(u32x4, v);
 }
 
+struct StageWeakArgs {
+  const _Float16 *weak_w;   // [d_out_pad][kp]
+  u32x4 *wst;               // [n_rt][2][kp32][64 lanes] units of 8 fp16
+  int kp, kp32, n_rt;
+};
+
+// The weak columns in the same operand order: lane % 32 = weak column of the tile, rows as above.
+__global__ __launch_bounds__(256) void owq_bwd_stage_weak(const StageWeakArgs a) {
+  const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long total = (long long)a.n_rt * 2 * a.kp32 * 64;
+  if (u >= total) return;
+  const int l = (int)(u & 63);
+  const long long q = u >> 6;
+  const int tt = (int)(q % a.kp32), s = (int)((q / a.kp32) & 1), rt = (int)(q / a.kp32 / 2);
+  const int t = 32 * tt + (l & 31), h = l >> 5;
+  h8_t v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int i = 32 * rt + 16 * s + 4 * h + (e & 3) + 8 * (e >> 2);     // below d_out_pad; padded rows hold 0
+    v[e] = t < a.kp ? a.weak_w[(size_t)i * a.kp + t] : (_Float16)0.f;
+  }
+  a.wst[u] = __builtin_bit_cast(u32x4, v);
+}
+
 struct ProdArgs {
   const u32 *codes;     // dwords of the packed tiles
   const u32 *sz;        // [G][d_out_pad] step size | zero point << 16
   const u32x4 *a_st;
   float *part;          // [split][128][d_in_pad]
-  int n_rt, nbp, chunks, d_out_pad, d_in_pad, blocks_per_group, n_groups, split, rt_per_split;
+  const u32x4 *wst;     // staged weak columns, or nullptr: the weak columns of dx are not made here
+  float *pw;            // [split][128][32 kp32]: their partial results
+  int n_rt, nbp, chunks, d_out_pad, d_in_pad, blocks_per_group, n_groups, split, rt_per_split, kp32;
 };
 
-template <int BITS>
+// HAS_W: the weak columns of dx ride along (every workgroup does the matrix instruction, those
+// without a tile of weak columns on a tile they do not store: a branch around it costs more).
+template <int BITS, bool HAS_W>
 __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs a) {
   __shared__ float zbuf[kBwdWaves][4][32];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, n32 = lane & 31;
@@ -106,16 +137,47 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][c][r] = 0.f;
   float zacc[4] = {0.f, 0.f, 0.f, 0.f};
-  constexpr int kDw = BITS == 3 ? 3 : 4;                              // dwords of the lane that hold this wave's columns
-  for (int rt = rt0; rt < rt1; ++rt) {
-    // codes of K-steps 4 w .. 4 w + 3 of the lane: dwords kDw w .. kDw w + kDw - 1 of its 12 or 16
-    const size_t tile = (size_t)rt * a.nbp + bp;
-    u32 cw[4] = {0u, 0u, 0u, 0u};
+  // Weak columns of dx: the workgroup of block pair bp also takes tile bp of the weak columns
+  // (32 of them), each of its waves one tile of 32 tokens, from the same staged dy, unscaled.
+  const bool has_w = HAS_W && bp < a.kp32;
+  const int wtile = HAS_W ? (bp < a.kp32 ? bp : 0) : 0;
+  f16_t wacc;
 #pragma unroll
-    for (int v = 0; v < kDw; ++v) {
-      const int dwi = kDw * w + v;
-      cw[v] = a.codes[((tile * a.chunks + (dwi >> 2)) * 64 + lane) * 4 + (dwi & 3)];
+  for (int r = 0; r < 16; ++r) wacc[r] = 0.f;
+  constexpr int kDw = BITS == 3 ? 3 : 4;                              // dwords of the lane that hold this wave's columns
+  // Everything one row tile needs from memory; the next tile's is fetched while this one is worked on.
+  struct Fetched {
+    u32 cw[4];          // codes of K-steps 4 w .. 4 w + 3 of the lane: dwords kDw w .. of its 12 or 16
+    u32x4 q[2][2];      // step sizes and zero points of the lane's eight rows of either half
+    u32x4 raw[2][4];    // staged dy of the four token tiles
+    u32x4 wsu[2];       // staged weak columns
+    u32x4 raww[2];      // staged dy of token tile w once more (unscaled operand of the weak product)
+  };
+  auto fetch = [&](Fetched &f, int rt) __attribute__((always_inline)) {
+    const size_t tile = (size_t)rt * a.nbp + bp;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int dwi = kDw * w + (v < kDw ? v : 0);
+      f.cw[v] = a.codes[((tile * a.chunks + (dwi >> 2)) * 64 + lane) * 4 + (dwi & 3)];
     }
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int i0 = 32 * rt + 16 * s + 4 * h;
+      f.q[s][0] = *reinterpret_cast<const u32x4 *>(sz + i0);
+      f.q[s][1] = *reinterpret_cast<const u32x4 *>(sz + i0 + 8);
+#pragma unroll
+      for (int m = 0; m < 4; ++m) f.raw[s][m] = a.a_st[(((size_t)rt * 2 + s) * 4 + m) * 64 + lane];
+      if (HAS_W) {
+        f.wsu[s] = a.wst[(((size_t)rt * 2 + s) * a.kp32 + wtile) * 64 + lane];
+        f.raww[s] = a.a_st[(((size_t)rt * 2 + s) * 4 + w) * 64 + lane];
+      }
+    }
+  };
+  Fetched cur, nxt;
+  fetch(cur, rt0 < a.n_rt ? rt0 : a.n_rt - 1);
+  for (int rt = rt0; rt < rt1; ++rt) {
+    fetch(nxt, rt + 1 < rt1 ? rt + 1 : rt);          // past the range: this tile again, unused
+    __builtin_amdgcn_sched_barrier(0);               // the loads above go out before the work below
     // turned codes of the two column tiles: B operands for both halves of the 32 rows
     h8_t wb[2][2];
 #pragma unroll
@@ -124,11 +186,11 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
 #pragma unroll
       for (int r = 0; r < 16; ++r) t[r] = cneg[c];
       if (c == 0) {
-        t = mma(a_operand<BITS, 0>(cw, M), sel0, t);
-        t = mma(a_operand<BITS, 1>(cw, M), sel1, t);
+        t = mma(a_operand<BITS, 0>(cur.cw, M), sel0, t);
+        t = mma(a_operand<BITS, 1>(cur.cw, M), sel1, t);
       } else {
-        t = mma(a_operand<BITS, 2>(cw, M), sel0, t);
-        t = mma(a_operand<BITS, 3>(cw, M), sel1, t);
+        t = mma(a_operand<BITS, 2>(cur.cw, M), sel0, t);
+        t = mma(a_operand<BITS, 3>(cur.cw, M), sel1, t);
       }
 #pragma unroll
       for (int s = 0; s < 2; ++s)
@@ -137,9 +199,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
     }
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      // step sizes and zero points of the lane's eight rows of this half
-      const int i0 = 32 * rt + 16 * s + 4 * h;
-      const u32x4 q0 = *reinterpret_cast<const u32x4 *>(sz + i0), q1 = *reinterpret_cast<const u32x4 *>(sz + i0 + 8);
+      const u32x4 q0 = cur.q[s][0], q1 = cur.q[s][1];
       const u32 d[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
       u32 sp2[4], zp2[4];
 #pragma unroll
@@ -147,9 +207,11 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
         sp2[p] = __builtin_amdgcn_perm(d[2 * p + 1], d[2 * p], 0x05040100u);   // (lo of even, lo of odd)
         zp2[p] = __builtin_amdgcn_perm(d[2 * p + 1], d[2 * p], 0x07060302u);   // (hi of even, hi of odd)
       }
+      if (HAS_W)
+        wacc = mma(__builtin_bit_cast(h8_t, cur.raww[s]), __builtin_bit_cast(h8_t, cur.wsu[s]), wacc);
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
-        const u32x4 raw = a.a_st[(((size_t)rt * 2 + s) * 4 + m) * 64 + lane];
+        const u32x4 raw = cur.raw[s][m];
         const u32 r[4] = {raw.x, raw.y, raw.z, raw.w};
         u32 ap[4];
 #pragma unroll
@@ -164,6 +226,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
         acc[m][1] = mma(aop, wb[1][s], acc[m][1]);
       }
     }
+    cur = nxt;
   }
   // zero-point term of every token: both halves of the rows, then from the operand layout
   // (token = lane % 32) to the accumulator layout (tokens along the registers)
@@ -187,23 +250,46 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
         part[(size_t)(32 * m + nl) * a.d_in_pad + j] = acc[m][c][r] - zbuf[w][m][nl];
       }
     }
+  if (has_w) {
+    float *pw = a.pw + (size_t)sp * kPassTokens * (32 * a.kp32);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int nl = 8 * (r >> 2) + 4 * h + (r & 3);
+      pw[(size_t)(32 * w + nl) * (32 * a.kp32) + 32 * bp + n32] = wacc[r];
+    }
+  }
 }
 
 struct SumArgs {
   const float *part;    // [split][128][d_in_pad]
+  const float *pw;      // [split][128][32 kp32], or nullptr
   const uint8_t *wmask; // bit j = column j is weak
+  const int *weak_idx;
   _Float16 *dx;         // [batch][d_in]
-  int d_in, d_in_pad, split, n0, ntok;
+  int d_in, d_in_pad, split, n0, ntok, k, kp32, dense_blocks;
 };
 
-// dx of the columns that are not weak: the partial results added in a fixed order.
+// dx: the partial results added in a fixed order.  Blocks below dense_blocks take 256 columns
+// each and skip the weak ones; the blocks after them take 256 weak columns each.
 __global__ __launch_bounds__(256) void owq_bwd_sum(const SumArgs a) {
-  const int j = blockIdx.x * 256 + threadIdx.x, nl = blockIdx.y;
-  if (j >= a.d_in || nl >= a.ntok) return;
-  if ((a.wmask[j >> 3] >> (j & 7)) & 1) return;
-  float v = 0.f;
-  for (int s = 0; s < a.split; ++s) v += a.part[((size_t)s * kPassTokens + nl) * a.d_in_pad + j];
-  a.dx[(size_t)(a.n0 + nl) * a.d_in + j] = (_Float16)v;
+  const int nl = blockIdx.y;
+  if (nl >= a.ntok) return;
+  if ((int)blockIdx.x < a.dense_blocks) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= a.d_in) return;
+    if ((a.wmask[j >> 3] >> (j & 7)) & 1) return;
+    float v = 0.f;
+    for (int s = 0; s < a.split; ++s) v += a.part[((size_t)s * kPassTokens + nl) * a.d_in_pad + j];
+    a.dx[(size_t)(a.n0 + nl) * a.d_in + j] = (_Float16)v;
+  } else {
+    const int t = ((int)blockIdx.x - a.dense_blocks) * 256 + threadIdx.x;
+    if (a.pw == nullptr || t >= a.k) return;
+    const int col = a.weak_idx[t];
+    if ((unsigned)col >= (unsigned)a.d_in) return;
+    float v = 0.f;
+    for (int s = 0; s < a.split; ++s) v += a.pw[((size_t)s * kPassTokens + nl) * (32 * a.kp32) + t];
+    a.dx[(size_t)(a.n0 + nl) * a.d_in + col] = (_Float16)v;
+  }
 }
 
 struct WeakArgs {
@@ -253,42 +339,94 @@ __global__ __launch_bounds__(256) void owq_bwd_weak(const WeakArgs a) {
   }
 }
 
-struct DwwArgs {
-  const _Float16 *dy, *x;
+struct StageXArgs {
+  const _Float16 *x;         // [batch][d_in]
   const int *weak_idx;
-  float *dww;                // [d_out][k]
-  int d_out, d_in, k, batch;
+  u32x4 *xw_st;              // [token steps of 16][kp32][64 lanes] units of 8 fp16
+  int d_in, k, kp32, batch, steps;
 };
 
-// dww: one thread per row, 8 weak columns per workgroup, the whole batch in order.
+// The activations at the weak columns as A operands with the tokens on the contraction axis:
+// lane % 32 = weak column of the tile, eight consecutive tokens per lane.
+__global__ __launch_bounds__(256) void owq_bwd_stage_x(const StageXArgs a) {
+  const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (u >= (long long)a.steps * a.kp32 * 64) return;
+  const int l = (int)(u & 63);
+  const long long q = u >> 6;
+  const int tt = (int)(q % a.kp32), ks = (int)(q / a.kp32);
+  const int t = 32 * tt + (l & 31), h = l >> 5;
+  int col = t < a.k ? a.weak_idx[t] : -1;
+  if ((unsigned)col >= (unsigned)a.d_in) col = -1;
+  h8_t v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int n = 16 * ks + 8 * h + e;
+    v[e] = (col >= 0 && n < a.batch) ? a.x[(size_t)n * a.d_in + col] : (_Float16)0.f;
+  }
+  a.xw_st[u] = __builtin_bit_cast(u32x4, v);
+}
+
+struct DwwArgs {
+  const _Float16 *dy;        // [batch][d_out]
+  const u32x4 *xw_st;
+  float *dww;                // [d_out][k]
+  int d_out, k, kp32, batch, steps;
+};
+
+// dww[i, t] = sum_n x[n, idx[t]] dy[n, i] on the matrix cores: a workgroup owns 32 rows i and up
+// to four tiles of 32 weak columns; its four waves deal the token steps among them and add
+// their results through LDS in a fixed order.
 __global__ __launch_bounds__(256) void owq_bwd_dww(const DwwArgs a) {
-  const int i = blockIdx.x * 256 + threadIdx.x, t0 = blockIdx.y * 8;
-  int col[8];
+  __shared__ float red[4][16][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5;
+  const int i = blockIdx.x * 32 + (lane & 31), tt0 = blockIdx.y * 4;
+  const int ntt = a.kp32 - tt0 < 4 ? a.kp32 - tt0 : 4;
+  const int ic = i < a.d_out ? i : a.d_out - 1;
+  f16_t acc[4];
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    const int c = t0 + t < a.k ? a.weak_idx[t0 + t] : 0;
-    col[t] = (unsigned)c < (unsigned)a.d_in ? c : 0;
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+  for (int ks = w; ks < a.steps; ks += 4) {
+    h8_t b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int n = 16 * ks + 8 * h + e;
+      const _Float16 v = a.dy[(size_t)(n < a.batch ? n : a.batch - 1) * a.d_out + ic];
+      b[e] = (n < a.batch && i < a.d_out) ? v : (_Float16)0.f;
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const u32x4 xa = a.xw_st[((size_t)ks * a.kp32 + (c < ntt ? tt0 + c : tt0)) * 64 + lane];
+      acc[c] = mma(__builtin_bit_cast(h8_t, xa), b, acc[c]);
+    }
   }
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const int ii = i < a.d_out ? i : a.d_out - 1;
-  for (int n = 0; n < a.batch; ++n) {
-    const float d = (float)a.dy[(size_t)n * a.d_out + ii];
-    const _Float16 *xr = a.x + (size_t)n * a.d_in;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) acc[t] = __builtin_fmaf(d, (float)xr[col[t]], acc[t]);
+  for (int c = 0; c < 4; ++c) {
+    __syncthreads();                                 // every thread, every round: the trip count is fixed
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[w][r][lane] = acc[c][r];
+    __syncthreads();
+    if (c < ntt) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r = 4 * w + q;                     // this thread's share of the 16 x 64 results
+        const float v = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
+        const int t = 32 * (tt0 + c) + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (i < a.d_out && t < a.k) a.dww[(size_t)i * a.k + t] = v;
+      }
+    }
   }
-  if (i < a.d_out)
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-      if (t0 + t < a.k) a.dww[(size_t)i * a.k + t0 + t] = acc[t];
 }
 
 struct BwdPlan {
-  int split, rt_per_split;
-  size_t a_st_bytes, part_bytes, total;
+  int split, rt_per_split, kp32;
+  bool weak_in_product;          // every tile of 32 weak columns finds a block pair's workgroup
+  int x_steps;                   // steps of 16 tokens of the whole batch
+  size_t a_st_bytes, part_bytes, wst_bytes, pw_bytes, xw_bytes, total;
 };
 
-BwdPlan plan(const owq_layer_info_t &g) {
+BwdPlan plan(const owq_layer_info_t &g, int batch) {
   BwdPlan p;
   // enough workgroups for the chip, few enough ranges that the partial results stay small
   int split = (512 + g.nbp - 1) / g.nbp;
@@ -299,7 +437,13 @@ BwdPlan plan(const owq_layer_info_t &g) {
   p.split = (g.n_rt + p.rt_per_split - 1) / p.rt_per_split;
   p.a_st_bytes = (size_t)g.n_rt * 2 * 4 * 64 * 16;
   p.part_bytes = (size_t)p.split * kPassTokens * ((size_t)g.nbp * 256) * 4;
-  p.total = p.a_st_bytes + p.part_bytes;
+  p.kp32 = (g.kp + 31) / 32;
+  p.weak_in_product = g.k > 0 && p.kp32 <= g.nbp;
+  p.wst_bytes = p.weak_in_product ? (size_t)g.n_rt * 2 * p.kp32 * 64 * 16 : 0;
+  p.pw_bytes = p.weak_in_product ? (size_t)p.split * kPassTokens * 32 * p.kp32 * 4 : 0;
+  p.x_steps = (batch + 15) / 16;
+  p.xw_bytes = g.k > 0 ? (size_t)p.x_steps * p.kp32 * 64 * 16 : 0;
+  p.total = p.a_st_bytes + p.part_bytes + p.wst_bytes + p.pw_bytes + p.xw_bytes;
   return p;
 }
 
@@ -314,7 +458,7 @@ extern "C" owq_status_t owq_backward_workspace_bytes(owq_handle_t h, int32_t bat
   if (h->info.layout != OWQ_LAYOUT_TILE) return OWQ_ERR_LAYOUT;
   if (!bytes) return OWQ_ERR_NULL;
   if (batch < 0 || batch > OWQ_MAX_BATCH) return OWQ_ERR_BATCH;
-  *bytes = plan(h->info).total;
+  *bytes = plan(h->info, batch).total;
   return OWQ_OK;
 }
 
@@ -326,17 +470,26 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
   if (g.layout != OWQ_LAYOUT_TILE) return OWQ_ERR_LAYOUT;
   if (batch < 0 || batch > OWQ_MAX_BATCH) return OWQ_ERR_BATCH;
   if (batch == 0 || (!dx && !dww)) return OWQ_OK;
-  if (!dy || (dww && g.k > 0 && !x) || (dx && !workspace)) return OWQ_ERR_NULL;
-  const BwdPlan p = plan(g);
-  if (dx && workspace_bytes < p.total) return OWQ_ERR_BUFFER;
+  if (!dy || (dww && g.k > 0 && !x) || !workspace) return OWQ_ERR_NULL;
+  const BwdPlan p = plan(g, batch);
+  if (workspace_bytes < p.total) return OWQ_ERR_BUFFER;
   if (((uintptr_t)dy | (uintptr_t)x | (uintptr_t)dx | (uintptr_t)dww) & 15u) return OWQ_ERR_BUFFER;
-  if (dx && ((uintptr_t)workspace & 255u)) return OWQ_ERR_BUFFER;
+  if ((uintptr_t)workspace & 255u) return OWQ_ERR_BUFFER;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const uint8_t *blob = static_cast<const uint8_t *>(h->dev_buf);
   hipError_t err = hipSuccess;
   if (dx) {
     u32x4 *a_st = static_cast<u32x4 *>(workspace);
     float *part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes);
+    u32x4 *wst = nullptr;
+    float *pw = nullptr;
+    if (p.weak_in_product) {
+      wst = reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes + p.part_bytes);
+      pw = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes + p.part_bytes + p.wst_bytes);
+      StageWeakArgs sw = {reinterpret_cast<const _Float16 *>(blob + g.off_weak_w), wst, g.kp, p.kp32, g.n_rt};
+      const long long wu = (long long)g.n_rt * 2 * p.kp32 * 64;
+      hipLaunchKernelGGL(owq_bwd_stage_weak, dim3((unsigned)((wu + 255) / 256)), dim3(256), 0, st, sw);
+    }
     for (int n0 = 0; n0 < batch && err == hipSuccess; n0 += kPassTokens) {
       const int ntok = batch - n0 < kPassTokens ? batch - n0 : kPassTokens;
       StageArgs sa = {static_cast<const _Float16 *>(dy), a_st, g.d_out, g.n_rt, n0, batch};
@@ -347,6 +500,9 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
       pa.sz = reinterpret_cast<const u32 *>(blob + g.off_sz);
       pa.a_st = a_st;
       pa.part = part;
+      pa.wst = wst;
+      pa.pw = pw;
+      pa.kp32 = p.kp32;
       pa.n_rt = g.n_rt;
       pa.nbp = g.nbp;
       pa.chunks = g.chunks;
@@ -357,11 +513,16 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
       pa.split = p.split;
       pa.rt_per_split = p.rt_per_split;
       const dim3 grid((unsigned)(g.nbp * p.split));
-      if (g.bits == 3) hipLaunchKernelGGL(owq_bwd_product<3>, grid, dim3(kBwdWaves * 64), 0, st, pa);
-      else hipLaunchKernelGGL(owq_bwd_product<4>, grid, dim3(kBwdWaves * 64), 0, st, pa);
-      SumArgs su = {part, blob + g.off_wmask, static_cast<_Float16 *>(dx), g.d_in, g.nbp * 256, p.split, n0, ntok};
-      hipLaunchKernelGGL(owq_bwd_sum, dim3((unsigned)((g.d_in + 255) / 256), (unsigned)ntok), dim3(256), 0, st, su);
-      if (g.k > 0) {
+      const dim3 block(kBwdWaves * 64);
+      if (g.bits == 3 && p.weak_in_product) hipLaunchKernelGGL((owq_bwd_product<3, true>), grid, block, 0, st, pa);
+      else if (g.bits == 3) hipLaunchKernelGGL((owq_bwd_product<3, false>), grid, block, 0, st, pa);
+      else if (p.weak_in_product) hipLaunchKernelGGL((owq_bwd_product<4, true>), grid, block, 0, st, pa);
+      else hipLaunchKernelGGL((owq_bwd_product<4, false>), grid, block, 0, st, pa);
+      const int dense_blocks = (g.d_in + 255) / 256, weak_blocks = p.weak_in_product ? (g.k + 255) / 256 : 0;
+      SumArgs su = {part, pw, blob + g.off_wmask, reinterpret_cast<const int *>(blob + g.off_weak_idx),
+                    static_cast<_Float16 *>(dx), g.d_in, g.nbp * 256, p.split, n0, ntok, g.k, p.kp32, dense_blocks};
+      hipLaunchKernelGGL(owq_bwd_sum, dim3((unsigned)(dense_blocks + weak_blocks), (unsigned)ntok), dim3(256), 0, st, su);
+      if (g.k > 0 && !p.weak_in_product) {
         WeakArgs wa = {static_cast<const _Float16 *>(dy), reinterpret_cast<const _Float16 *>(blob + g.off_weak_w),
                        reinterpret_cast<const int *>(blob + g.off_weak_idx), static_cast<_Float16 *>(dx),
                        g.d_out, g.d_in, g.kp, n0, ntok};
@@ -371,9 +532,14 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
     }
   }
   if (dww && g.k > 0 && err == hipSuccess) {
-    DwwArgs da = {static_cast<const _Float16 *>(dy), static_cast<const _Float16 *>(x),
-                  reinterpret_cast<const int *>(blob + g.off_weak_idx), dww, g.d_out, g.d_in, g.k, batch};
-    hipLaunchKernelGGL(owq_bwd_dww, dim3((unsigned)((g.d_out + 255) / 256), (unsigned)((g.k + 7) / 8)), dim3(256), 0, st, da);
+    u32x4 *xw_st = reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes + p.part_bytes +
+                                             p.wst_bytes + p.pw_bytes);
+    StageXArgs sx = {static_cast<const _Float16 *>(x), reinterpret_cast<const int *>(blob + g.off_weak_idx), xw_st,
+                     g.d_in, g.k, p.kp32, batch, p.x_steps};
+    const long long xu = (long long)p.x_steps * p.kp32 * 64;
+    hipLaunchKernelGGL(owq_bwd_stage_x, dim3((unsigned)((xu + 255) / 256)), dim3(256), 0, st, sx);
+    DwwArgs da = {static_cast<const _Float16 *>(dy), xw_st, dww, g.d_out, g.k, p.kp32, batch, p.x_steps};
+    hipLaunchKernelGGL(owq_bwd_dww, dim3((unsigned)((g.d_out + 31) / 32), (unsigned)((p.kp32 + 3) / 4)), dim3(256), 0, st, da);
     err = hipGetLastError();
   }
   if (err != hipSuccess) {

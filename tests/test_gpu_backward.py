@@ -72,6 +72,9 @@ CASES = [
     ("one_token", 1024, 256, 3, 128, 9, 1),
     ("two_passes", 512, 64, 4, 128, 8, 130),        # 128 + 2 tokens
     ("three_passes", 256, 96, 3, 0, 3, 300),
+    ("more_weak_tiles_than_block_pairs", 256, 96, 4, 0, 40, 11),   # the plain kernel for the weak columns of dx
+    ("three_weak_tiles", 1024, 128, 3, 128, 70, 35),
+    ("six_weak_tiles", 2048, 64, 4, 128, 170, 20),       # dww in two groups of tiles
     ("many_rows", 256, 2048, 3, 128, 4, 40),        # several ranges of rows per block pair
 ]
 
