@@ -297,8 +297,8 @@ owq_status_t owq_search_config(const owq_search_desc_t *desc, const uint16_t *w,
  * is NULL), dx fp16 [batch][d_in] (written; NULL = not wanted), dww fp32 [d_out][k] (written,
  * summed over the whole batch; NULL = not wanted), workspace of at least
  * owq_backward_workspace_bytes bytes for this batch, 256-byte aligned (contents undefined before and after;
- * calls that share a workspace must not overlap).  fp32 accumulation; dy times the step size is
- * rounded to fp16 once before the product (relative 2^-11 per term); dx is rounded to fp16
+ * calls that share a workspace must not overlap).  fp32 accumulation; dy times the step size
+ * is rounded to fp16 once before the product (relative 2^-11 per term); dx is rounded to fp16
  * once.  Work is queued on `stream`, nothing is allocated, nothing synchronises.
  * Errors: OWQ_ERR_HANDLE, OWQ_ERR_LAYOUT, OWQ_ERR_NULL, OWQ_ERR_BATCH, OWQ_ERR_BUFFER (workspace
  * too small, a pointer misaligned), OWQ_ERR_HIP.  batch == 0 is a no-op.

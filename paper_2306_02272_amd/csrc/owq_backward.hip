@@ -35,6 +35,7 @@ namespace {
 constexpr int kPassTokens = 128;     // tokens per pass: four accumulator tiles of 32 per wave
 constexpr int kBwdWaves = 4;         // one per quarter of a tile's 256 columns
 constexpr int kSplitMax = 16;        // most ranges of rows per block pair
+constexpr int kLaunchPasses = 4;     // passes (of 128 tokens) that one set of launches takes
 
 // bit offset of the pair of codes that column c (0..15) of K-step t holds, as in the packer
 __device__ const signed char kPairOffset3[4][4] = {{0, 3, 6, 1}, {4, 7, 2, 5}, {0, 3, 6, 1}, {4, 7, 4, 7}};
@@ -42,18 +43,20 @@ __device__ const signed char kPairOffset4[4] = {0, 4, 2, 6};
 
 struct StageArgs {
   const _Float16 *dy;   // [batch][d_out]
-  u32x4 *a_st;          // [n_rt][2][4 token tiles][64 lanes] units of 8 fp16
-  int d_out, n_rt, n0, batch;
+  u32x4 *a_st;          // [pass][n_rt][2][4 token tiles][64 lanes] units of 8 fp16
+  int d_out, n_rt, n0, batch, passes;
 };
 
 // One thread per unit: token 32 m + lane % 32 of the pass, rows 32 rt + 16 s + 4 h + {0..3} and
 // the same + 8 (h = lane / 32): the order in which the turned codes hold their rows.
 __global__ __launch_bounds__(256) void owq_bwd_stage(const StageArgs a) {
   const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long total = (long long)a.n_rt * 2 * 4 * 64;
-  if (u >= total) return;
-  const int l = (int)(u & 63), m = (int)((u >> 6) & 3), s = (int)((u >> 8) & 1), rt = (int)(u >> 9);
-  const int n = a.n0 + 32 * m + (l & 31), h = l >> 5;
+  const long long per_pass = (long long)a.n_rt * 2 * 4 * 64;
+  if (u >= per_pass * a.passes) return;
+  const int pass = (int)(u / per_pass);
+  const long long v0 = u - pass * per_pass;
+  const int l = (int)(v0 & 63), m = (int)((v0 >> 6) & 3), s = (int)((v0 >> 8) & 1), rt = (int)(v0 >> 9);
+  const int n = a.n0 + kPassTokens * pass + 32 * m + (l & 31), h = l >> 5;
   h8_t v;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -103,7 +106,14 @@ template <int BITS, bool HAS_W>
 __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs a) {
   __shared__ float zbuf[kBwdWaves][4][32];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, n32 = lane & 31;
-  const int bp = blockIdx.x % a.nbp, sp = blockIdx.x / a.nbp;
+  // Workgroups go to the eight dies (each with its own L2) in turn.  The workgroups that read the
+  // same rows of the staged dy (same pass, same range of rows, different block pairs) are given
+  // ids that land on one die: die d takes a contiguous eighth of the (pass, range, block pair) order.
+  int id = blockIdx.x;
+  const int total = gridDim.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  const int bp = id % a.nbp, sp = (id / a.nbp) % a.split, pass = id / (a.nbp * a.split);
+  const u32x4 *a_st = a.a_st + (size_t)pass * a.n_rt * 512;
   const int rt0 = sp * a.rt_per_split;
   const int rt1 = rt0 + a.rt_per_split < a.n_rt ? rt0 + a.rt_per_split : a.n_rt;
   Magic M;
@@ -166,40 +176,40 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
       f.q[s][0] = *reinterpret_cast<const u32x4 *>(sz + i0);
       f.q[s][1] = *reinterpret_cast<const u32x4 *>(sz + i0 + 8);
 #pragma unroll
-      for (int m = 0; m < 4; ++m) f.raw[s][m] = a.a_st[(((size_t)rt * 2 + s) * 4 + m) * 64 + lane];
+      for (int m = 0; m < 4; ++m) f.raw[s][m] = a_st[(((size_t)rt * 2 + s) * 4 + m) * 64 + lane];
       if (HAS_W) {
         f.wsu[s] = a.wst[(((size_t)rt * 2 + s) * a.kp32 + wtile) * 64 + lane];
-        f.raww[s] = a.a_st[(((size_t)rt * 2 + s) * 4 + w) * 64 + lane];
+        f.raww[s] = a_st[(((size_t)rt * 2 + s) * 4 + w) * 64 + lane];
       }
     }
   };
-  Fetched cur, nxt;
-  fetch(cur, rt0 < a.n_rt ? rt0 : a.n_rt - 1);
-  for (int rt = rt0; rt < rt1; ++rt) {
-    fetch(nxt, rt + 1 < rt1 ? rt + 1 : rt);          // past the range: this tile again, unused
-    __builtin_amdgcn_sched_barrier(0);               // the loads above go out before the work below
+  auto work = [&](const Fetched &f) __attribute__((always_inline)) {
     // turned codes of the two column tiles: B operands for both halves of the 32 rows
-    h8_t wb[2][2];
+    u32x4 wb[2][2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       f16_t t;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) t[r] = cneg[c];
+      for (int r = 0; r < 16; ++r) t[r] = cneg[c];    // start from minus the unpack constant
       if (c == 0) {
-        t = mma(a_operand<BITS, 0>(cur.cw, M), sel0, t);
-        t = mma(a_operand<BITS, 1>(cur.cw, M), sel1, t);
+        t = mma(a_operand<BITS, 0>(f.cw, M), sel0, t);
+        t = mma(a_operand<BITS, 1>(f.cw, M), sel1, t);
       } else {
-        t = mma(a_operand<BITS, 2>(cur.cw, M), sel0, t);
-        t = mma(a_operand<BITS, 3>(cur.cw, M), sel1, t);
+        t = mma(a_operand<BITS, 2>(f.cw, M), sel0, t);
+        t = mma(a_operand<BITS, 3>(f.cw, M), sel1, t);
       }
 #pragma unroll
-      for (int s = 0; s < 2; ++s)
+      for (int s = 0; s < 2; ++s) {
+        u32 pk[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) wb[c][s][e] = (_Float16)t[8 * s + e];
+        for (int e = 0; e < 4; ++e)       // small integers: exact whatever the rounding
+          pk[e] = __builtin_bit_cast(u32, __builtin_amdgcn_cvt_pkrtz(t[8 * s + 2 * e], t[8 * s + 2 * e + 1]));
+        wb[c][s] = (u32x4){pk[0], pk[1], pk[2], pk[3]};
+      }
     }
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      const u32x4 q0 = cur.q[s][0], q1 = cur.q[s][1];
+      const u32x4 q0 = f.q[s][0], q1 = f.q[s][1];
       const u32 d[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
       u32 sp2[4], zp2[4];
 #pragma unroll
@@ -208,10 +218,10 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
         zp2[p] = __builtin_amdgcn_perm(d[2 * p + 1], d[2 * p], 0x07060302u);   // (hi of even, hi of odd)
       }
       if (HAS_W)
-        wacc = mma(__builtin_bit_cast(h8_t, cur.raww[s]), __builtin_bit_cast(h8_t, cur.wsu[s]), wacc);
+        wacc = mma(__builtin_bit_cast(h8_t, f.raww[s]), __builtin_bit_cast(h8_t, f.wsu[s]), wacc);
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
-        const u32x4 raw = cur.raw[s][m];
+        const u32x4 raw = f.raw[s][m];
         const u32 r[4] = {raw.x, raw.y, raw.z, raw.w};
         u32 ap[4];
 #pragma unroll
@@ -222,10 +232,18 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
         }
         const u32x4 av = {ap[0], ap[1], ap[2], ap[3]};
         const h8_t aop = __builtin_bit_cast(h8_t, av);
-        acc[m][0] = mma(aop, wb[0][s], acc[m][0]);
-        acc[m][1] = mma(aop, wb[1][s], acc[m][1]);
+        acc[m][0] = mma(aop, __builtin_bit_cast(h8_t, wb[0][s]), acc[m][0]);
+        acc[m][1] = mma(aop, __builtin_bit_cast(h8_t, wb[1][s]), acc[m][1]);
       }
     }
+  };
+  // the tile after the one being worked on is in flight
+  Fetched cur, nxt;
+  fetch(cur, rt0 < a.n_rt ? rt0 : a.n_rt - 1);
+  for (int rt = rt0; rt < rt1; ++rt) {
+    fetch(nxt, rt + 1 < rt1 ? rt + 1 : rt);          // past the range: this tile again, unused
+    __builtin_amdgcn_sched_barrier(0);               // the loads above go out before the work below
+    work(cur);
     cur = nxt;
   }
   // zero-point term of every token: both halves of the rows, then from the operand layout
@@ -238,7 +256,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  float *part = a.part + (size_t)sp * kPassTokens * a.d_in_pad;
+  float *part = a.part + ((size_t)pass * a.split + sp) * kPassTokens * a.d_in_pad;
 #pragma unroll
   for (int m = 0; m < 4; ++m)
 #pragma unroll
@@ -251,7 +269,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
       }
     }
   if (has_w) {
-    float *pw = a.pw + (size_t)sp * kPassTokens * (32 * a.kp32);
+    float *pw = a.pw + ((size_t)pass * a.split + sp) * kPassTokens * (32 * a.kp32);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int nl = 8 * (r >> 2) + 4 * h + (r & 3);
@@ -261,8 +279,8 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
 }
 
 struct SumArgs {
-  const float *part;    // [split][128][d_in_pad]
-  const float *pw;      // [split][128][32 kp32], or nullptr
+  const float *part;    // [pass][split][128][d_in_pad]
+  const float *pw;      // [pass][split][128][32 kp32], or nullptr
   const uint8_t *wmask; // bit j = column j is weak
   const int *weak_idx;
   _Float16 *dx;         // [batch][d_in]
@@ -272,23 +290,24 @@ struct SumArgs {
 // dx: the partial results added in a fixed order.  Blocks below dense_blocks take 256 columns
 // each and skip the weak ones; the blocks after them take 256 weak columns each.
 __global__ __launch_bounds__(256) void owq_bwd_sum(const SumArgs a) {
-  const int nl = blockIdx.y;
-  if (nl >= a.ntok) return;
+  if ((int)blockIdx.y >= a.ntok) return;
+  const int pass = blockIdx.y / kPassTokens, nl = blockIdx.y % kPassTokens;
+  const size_t base = (size_t)pass * a.split * kPassTokens;           // first (range, token) row of this pass
   if ((int)blockIdx.x < a.dense_blocks) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= a.d_in) return;
     if ((a.wmask[j >> 3] >> (j & 7)) & 1) return;
     float v = 0.f;
-    for (int s = 0; s < a.split; ++s) v += a.part[((size_t)s * kPassTokens + nl) * a.d_in_pad + j];
-    a.dx[(size_t)(a.n0 + nl) * a.d_in + j] = (_Float16)v;
+    for (int s = 0; s < a.split; ++s) v += a.part[(base + (size_t)s * kPassTokens + nl) * a.d_in_pad + j];
+    a.dx[(size_t)(a.n0 + blockIdx.y) * a.d_in + j] = (_Float16)v;
   } else {
     const int t = ((int)blockIdx.x - a.dense_blocks) * 256 + threadIdx.x;
     if (a.pw == nullptr || t >= a.k) return;
     const int col = a.weak_idx[t];
     if ((unsigned)col >= (unsigned)a.d_in) return;
     float v = 0.f;
-    for (int s = 0; s < a.split; ++s) v += a.pw[((size_t)s * kPassTokens + nl) * (32 * a.kp32) + t];
-    a.dx[(size_t)(a.n0 + nl) * a.d_in + col] = (_Float16)v;
+    for (int s = 0; s < a.split; ++s) v += a.pw[(base + (size_t)s * kPassTokens + nl) * (32 * a.kp32) + t];
+    a.dx[(size_t)(a.n0 + blockIdx.y) * a.d_in + col] = (_Float16)v;
   }
 }
 
@@ -420,6 +439,7 @@ __global__ __launch_bounds__(256) void owq_bwd_dww(const DwwArgs a) {
 }
 
 struct BwdPlan {
+  int passes;                    // passes per set of launches
   int split, rt_per_split, kp32;
   bool weak_in_product;          // every tile of 32 weak columns finds a block pair's workgroup
   int x_steps;                   // steps of 16 tokens of the whole batch
@@ -429,18 +449,20 @@ struct BwdPlan {
 BwdPlan plan(const owq_layer_info_t &g, int batch) {
   BwdPlan p;
   // enough workgroups for the chip, few enough ranges that the partial results stay small
-  int split = (512 + g.nbp - 1) / g.nbp;
+  const int all_passes = (batch + kPassTokens - 1) / kPassTokens;
+  p.passes = all_passes < kLaunchPasses ? (all_passes < 1 ? 1 : all_passes) : kLaunchPasses;
+  int split = (512 + g.nbp * p.passes - 1) / (g.nbp * p.passes);
   if (split > kSplitMax) split = kSplitMax;
   if (split > g.n_rt) split = g.n_rt;
   if (split < 1) split = 1;
   p.rt_per_split = (g.n_rt + split - 1) / split;
   p.split = (g.n_rt + p.rt_per_split - 1) / p.rt_per_split;
-  p.a_st_bytes = (size_t)g.n_rt * 2 * 4 * 64 * 16;
-  p.part_bytes = (size_t)p.split * kPassTokens * ((size_t)g.nbp * 256) * 4;
+  p.a_st_bytes = (size_t)p.passes * g.n_rt * 2 * 4 * 64 * 16;
+  p.part_bytes = (size_t)p.passes * p.split * kPassTokens * ((size_t)g.nbp * 256) * 4;
   p.kp32 = (g.kp + 31) / 32;
   p.weak_in_product = g.k > 0 && p.kp32 <= g.nbp;
   p.wst_bytes = p.weak_in_product ? (size_t)g.n_rt * 2 * p.kp32 * 64 * 16 : 0;
-  p.pw_bytes = p.weak_in_product ? (size_t)p.split * kPassTokens * 32 * p.kp32 * 4 : 0;
+  p.pw_bytes = p.weak_in_product ? (size_t)p.passes * p.split * kPassTokens * 32 * p.kp32 * 4 : 0;
   p.x_steps = (batch + 15) / 16;
   p.xw_bytes = g.k > 0 ? (size_t)p.x_steps * p.kp32 * 64 * 16 : 0;
   p.total = p.a_st_bytes + p.part_bytes + p.wst_bytes + p.pw_bytes + p.xw_bytes;
@@ -490,10 +512,12 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
       const long long wu = (long long)g.n_rt * 2 * p.kp32 * 64;
       hipLaunchKernelGGL(owq_bwd_stage_weak, dim3((unsigned)((wu + 255) / 256)), dim3(256), 0, st, sw);
     }
-    for (int n0 = 0; n0 < batch && err == hipSuccess; n0 += kPassTokens) {
-      const int ntok = batch - n0 < kPassTokens ? batch - n0 : kPassTokens;
-      StageArgs sa = {static_cast<const _Float16 *>(dy), a_st, g.d_out, g.n_rt, n0, batch};
-      const long long units = (long long)g.n_rt * 512;
+    const int per_launch = p.passes * kPassTokens;
+    for (int n0 = 0; n0 < batch && err == hipSuccess; n0 += per_launch) {
+      const int ntok = batch - n0 < per_launch ? batch - n0 : per_launch;
+      const int passes = (ntok + kPassTokens - 1) / kPassTokens;
+      StageArgs sa = {static_cast<const _Float16 *>(dy), a_st, g.d_out, g.n_rt, n0, batch, passes};
+      const long long units = (long long)g.n_rt * 512 * passes;
       hipLaunchKernelGGL(owq_bwd_stage, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, sa);
       ProdArgs pa;
       pa.codes = reinterpret_cast<const u32 *>(blob + g.off_codes);
@@ -512,7 +536,7 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
       pa.n_groups = g.n_groups;
       pa.split = p.split;
       pa.rt_per_split = p.rt_per_split;
-      const dim3 grid((unsigned)(g.nbp * p.split));
+      const dim3 grid((unsigned)(g.nbp * p.split * passes));
       const dim3 block(kBwdWaves * 64);
       if (g.bits == 3 && p.weak_in_product) hipLaunchKernelGGL((owq_bwd_product<3, true>), grid, block, 0, st, pa);
       else if (g.bits == 3) hipLaunchKernelGGL((owq_bwd_product<3, false>), grid, block, 0, st, pa);
