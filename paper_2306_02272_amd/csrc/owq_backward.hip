@@ -41,6 +41,20 @@ constexpr int kLaunchPasses = 4;     // passes (of 128 tokens) that one set of l
 __device__ const signed char kPairOffset3[4][4] = {{0, 3, 6, 1}, {4, 7, 2, 5}, {0, 3, 6, 1}, {4, 7, 4, 7}};
 __device__ const signed char kPairOffset4[4] = {0, 4, 2, 6};
 
+// N 2-byte loads whose results get a use of their own after all of them have been issued, so
+// that the compiler cannot move a load under the branch of a later select (loads under branches
+// are waited for one by one).  Every address must be valid whatever the selects decide.
+template <int N>
+__device__ __forceinline__ void load_h(const _Float16 *const (&p)[N], _Float16 (&out)[N]) {
+  u32 r[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) r[e] = __builtin_bit_cast(unsigned short, *p[e]);
+#pragma unroll
+  for (int e = 0; e < N; ++e) asm volatile("" : "+v"(r[e]));
+#pragma unroll
+  for (int e = 0; e < N; ++e) out[e] = __builtin_bit_cast(_Float16, (unsigned short)r[e]);
+}
+
 struct StageArgs {
   const _Float16 *dy;   // [batch][d_out]
   u32x4 *a_st;          // [pass][n_rt][2][4 token tiles][64 lanes] units of 8 fp16
@@ -58,10 +72,31 @@ __global__ __launch_bounds__(256) void owq_bwd_stage(const StageArgs a) {
   const int l = (int)(v0 & 63), m = (int)((v0 >> 6) & 3), s = (int)((v0 >> 8) & 1), rt = (int)(v0 >> 9);
   const int n = a.n0 + kPassTokens * pass + 32 * m + (l & 31), h = l >> 5;
   h8_t v;
+  const int ia = 32 * rt + 16 * s + 4 * h;          // rows ia .. ia + 3 and ia + 8 .. ia + 11
+  if (n < a.batch && ia + 11 < a.d_out && (a.d_out & 3) == 0) {
+    // both runs of four rows inside the matrix and 8-byte aligned (dy is 16-byte aligned)
+    typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+    const _Float16 *row = a.dy + (size_t)n * a.d_out + ia;
+    const h4_t lo = *reinterpret_cast<const h4_t *>(row), hi = *reinterpret_cast<const h4_t *>(row + 8);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int i = 32 * rt + 16 * s + 4 * h + (e & 3) + 8 * (e >> 2);
-    v[e] = (n < a.batch && i < a.d_out) ? a.dy[(size_t)n * a.d_out + i] : (_Float16)0.f;
+    for (int e = 0; e < 4; ++e) {
+      v[e] = lo[e];
+      v[4 + e] = hi[e];
+    }
+  } else {
+    const _Float16 *p[8];
+    _Float16 x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i = ia + (e & 3) + 8 * (e >> 2);
+      p[e] = a.dy + (size_t)(n < a.batch ? n : a.batch - 1) * a.d_out + (i < a.d_out ? i : a.d_out - 1);
+    }
+    load_h<8>(p, x);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i = ia + (e & 3) + 8 * (e >> 2);
+      v[e] = (n < a.batch && i < a.d_out) ? x[e] : (_Float16)0.f;
+    }
   }
   a.a_st[u] = __builtin_bit_cast(u32x4, v);
 }
@@ -82,11 +117,16 @@ __global__ __launch_bounds__(256) void owq_bwd_stage_weak(const StageWeakArgs a)
   const int tt = (int)(q % a.kp32), s = (int)((q / a.kp32) & 1), rt = (int)(q / a.kp32 / 2);
   const int t = 32 * tt + (l & 31), h = l >> 5;
   h8_t v;
+  const _Float16 *p[8];
+  _Float16 x[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int i = 32 * rt + 16 * s + 4 * h + (e & 3) + 8 * (e >> 2);     // below d_out_pad; padded rows hold 0
-    v[e] = t < a.kp ? a.weak_w[(size_t)i * a.kp + t] : (_Float16)0.f;
+    p[e] = a.weak_w + (size_t)i * a.kp + (t < a.kp ? t : a.kp - 1);
   }
+  load_h<8>(p, x);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = t < a.kp ? x[e] : (_Float16)0.f;
   a.wst[u] = __builtin_bit_cast(u32x4, v);
 }
 
@@ -287,19 +327,23 @@ struct SumArgs {
   int d_in, d_in_pad, split, n0, ntok, k, kp32, dense_blocks;
 };
 
-// dx: the partial results added in a fixed order.  Blocks below dense_blocks take 256 columns
+// dx: the partial results added in a fixed order.  Blocks below dense_blocks take 1024 columns
 // each and skip the weak ones; the blocks after them take 256 weak columns each.
 __global__ __launch_bounds__(256) void owq_bwd_sum(const SumArgs a) {
   if ((int)blockIdx.y >= a.ntok) return;
   const int pass = blockIdx.y / kPassTokens, nl = blockIdx.y % kPassTokens;
   const size_t base = (size_t)pass * a.split * kPassTokens;           // first (range, token) row of this pass
   if ((int)blockIdx.x < a.dense_blocks) {
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int j = (blockIdx.x * 256 + threadIdx.x) * 4;            // four columns per thread (d_in_pad is a multiple of 256)
     if (j >= a.d_in) return;
-    if ((a.wmask[j >> 3] >> (j & 7)) & 1) return;
-    float v = 0.f;
-    for (int s = 0; s < a.split; ++s) v += a.part[(base + (size_t)s * kPassTokens + nl) * a.d_in_pad + j];
-    a.dx[(size_t)(a.n0 + blockIdx.y) * a.d_in + j] = (_Float16)v;
+    f4_t v = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < a.split; ++s)
+      v += *reinterpret_cast<const f4_t *>(a.part + (base + (size_t)s * kPassTokens + nl) * a.d_in_pad + j);
+    const u32 weak = (a.wmask[j >> 3] >> (j & 7)) & 15u;          // j is a multiple of 4: the four bits sit in one byte
+    _Float16 *out = a.dx + (size_t)(a.n0 + blockIdx.y) * a.d_in + j;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (j + e < a.d_in && !((weak >> e) & 1u)) out[e] = (_Float16)v[e];
   } else {
     const int t = ((int)blockIdx.x - a.dense_blocks) * 256 + threadIdx.x;
     if (a.pw == nullptr || t >= a.k) return;
@@ -377,11 +421,16 @@ __global__ __launch_bounds__(256) void owq_bwd_stage_x(const StageXArgs a) {
   int col = t < a.k ? a.weak_idx[t] : -1;
   if ((unsigned)col >= (unsigned)a.d_in) col = -1;
   h8_t v;
+  const _Float16 *p[8];
+  _Float16 xv[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int n = 16 * ks + 8 * h + e;
-    v[e] = (col >= 0 && n < a.batch) ? a.x[(size_t)n * a.d_in + col] : (_Float16)0.f;
+    p[e] = a.x + (size_t)(n < a.batch ? n : a.batch - 1) * a.d_in + (col >= 0 ? col : 0);
   }
+  load_h<8>(p, xv);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (col >= 0 && 16 * ks + 8 * h + e < a.batch) ? xv[e] : (_Float16)0.f;
   a.xw_st[u] = __builtin_bit_cast(u32x4, v);
 }
 
@@ -392,47 +441,75 @@ struct DwwArgs {
   int d_out, k, kp32, batch, steps;
 };
 
-// dww[i, t] = sum_n x[n, idx[t]] dy[n, i] on the matrix cores: a workgroup owns 32 rows i and up
-// to four tiles of 32 weak columns; its four waves deal the token steps among them and add
-// their results through LDS in a fixed order.
+// dww[i, t] = sum_n x[n, idx[t]] dy[n, i] on the matrix cores: a workgroup owns 32 rows i and NTT
+// tiles of 32 weak columns; its four waves deal the token steps among them and add their results
+// through LDS in a fixed order.  The work is tiny and all latency: a wave sends out the loads of
+// eight of its token steps at once.
+template <int NTT>
 __global__ __launch_bounds__(256) void owq_bwd_dww(const DwwArgs a) {
   __shared__ float red[4][16][64];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5;
-  const int i = blockIdx.x * 32 + (lane & 31), tt0 = blockIdx.y * 4;
-  const int ntt = a.kp32 - tt0 < 4 ? a.kp32 - tt0 : 4;
+  const int i = blockIdx.x * 32 + (lane & 31), tt0 = blockIdx.y * NTT;
+  const int ntt = a.kp32 - tt0 < NTT ? a.kp32 - tt0 : NTT;
   const int ic = i < a.d_out ? i : a.d_out - 1;
-  f16_t acc[4];
+  f16_t acc[NTT];
 #pragma unroll
-  for (int c = 0; c < 4; ++c)
+  for (int c = 0; c < NTT; ++c)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
-  for (int ks = w; ks < a.steps; ks += 4) {
-    h8_t b;
+  constexpr int kSteps = 8;                          // token steps of a wave in flight together
+  for (int ks = w; ks < a.steps; ks += 4 * kSteps) {
+    h8_t b[kSteps];
+    u32x4 xa[kSteps][NTT];
+    const _Float16 *p[8 * kSteps];
+    _Float16 v[8 * kSteps];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int n = 16 * ks + 8 * h + e;
-      const _Float16 v = a.dy[(size_t)(n < a.batch ? n : a.batch - 1) * a.d_out + ic];
-      b[e] = (n < a.batch && i < a.d_out) ? v : (_Float16)0.f;
-    }
+    for (int u = 0; u < kSteps; ++u) {
+      const int k2 = ks + 4 * u;                     // k2 >= steps: tokens past the batch, zeros
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const u32x4 xa = a.xw_st[((size_t)ks * a.kp32 + (c < ntt ? tt0 + c : tt0)) * 64 + lane];
-      acc[c] = mma(__builtin_bit_cast(h8_t, xa), b, acc[c]);
+      for (int e = 0; e < 8; ++e) {
+        const int n = 16 * k2 + 8 * h + e;
+        p[8 * u + e] = a.dy + (size_t)(n < a.batch ? n : a.batch - 1) * a.d_out + ic;
+      }
+      const int kc = k2 < a.steps ? k2 : a.steps - 1;
+#pragma unroll
+      for (int c = 0; c < NTT; ++c) xa[u][c] = a.xw_st[((size_t)kc * a.kp32 + (c < ntt ? tt0 + c : tt0)) * 64 + lane];
     }
+    load_h<8 * kSteps>(p, v);
+#pragma unroll
+    for (int u = 0; u < kSteps; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        b[u][e] = (16 * (ks + 4 * u) + 8 * h + e < a.batch && i < a.d_out) ? v[8 * u + e] : (_Float16)0.f;
+#pragma unroll
+    for (int u = 0; u < kSteps; ++u)
+#pragma unroll
+      for (int c = 0; c < NTT; ++c) acc[c] = mma(__builtin_bit_cast(h8_t, xa[u][c]), b[u], acc[c]);
   }
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
+  for (int c = 0; c < NTT; ++c) {
     __syncthreads();                                 // every thread, every round: the trip count is fixed
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[w][r][lane] = acc[c][r];
     __syncthreads();
     if (c < ntt) {
+      // this thread's share of the 16 x 64 results: registers 4 w .. 4 w + 3 = four consecutive weak columns
+      f4_t v;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int r = 4 * w + q;                     // this thread's share of the 16 x 64 results
-        const float v = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
-        const int t = 32 * (tt0 + c) + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (i < a.d_out && t < a.k) a.dww[(size_t)i * a.k + t] = v;
+        const int r = 4 * w + q;
+        v[q] = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
+      }
+      const int t = 32 * (tt0 + c) + 8 * w + 4 * h;
+      if (i < a.d_out) {
+        float *out = a.dww + (size_t)i * a.k + t;
+        if ((a.k & 3) == 0 && t + 3 < a.k) {
+          *reinterpret_cast<f4_t *>(out) = v;        // 16-byte aligned: dww is, and k is a multiple of 4
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (t + q < a.k) out[q] = v[q];
+        }
       }
     }
   }
@@ -542,7 +619,7 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
       else if (g.bits == 3) hipLaunchKernelGGL((owq_bwd_product<3, false>), grid, block, 0, st, pa);
       else if (p.weak_in_product) hipLaunchKernelGGL((owq_bwd_product<4, true>), grid, block, 0, st, pa);
       else hipLaunchKernelGGL((owq_bwd_product<4, false>), grid, block, 0, st, pa);
-      const int dense_blocks = (g.d_in + 255) / 256, weak_blocks = p.weak_in_product ? (g.k + 255) / 256 : 0;
+      const int dense_blocks = (g.d_in + 1023) / 1024, weak_blocks = p.weak_in_product ? (g.k + 255) / 256 : 0;
       SumArgs su = {part, pw, blob + g.off_wmask, reinterpret_cast<const int *>(blob + g.off_weak_idx),
                     static_cast<_Float16 *>(dx), g.d_in, g.nbp * 256, p.split, n0, ntok, g.k, p.kp32, dense_blocks};
       hipLaunchKernelGGL(owq_bwd_sum, dim3((unsigned)(dense_blocks + weak_blocks), (unsigned)ntok), dim3(256), 0, st, su);
@@ -563,7 +640,10 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
     const long long xu = (long long)p.x_steps * p.kp32 * 64;
     hipLaunchKernelGGL(owq_bwd_stage_x, dim3((unsigned)((xu + 255) / 256)), dim3(256), 0, st, sx);
     DwwArgs da = {static_cast<const _Float16 *>(dy), xw_st, dww, g.d_out, g.k, p.kp32, batch, p.x_steps};
-    hipLaunchKernelGGL(owq_bwd_dww, dim3((unsigned)((g.d_out + 31) / 32), (unsigned)((p.kp32 + 3) / 4)), dim3(256), 0, st, da);
+    const unsigned rows32 = (unsigned)((g.d_out + 31) / 32);
+    if (p.kp32 == 1) hipLaunchKernelGGL(owq_bwd_dww<1>, dim3(rows32, 1), dim3(256), 0, st, da);
+    else if (p.kp32 == 2) hipLaunchKernelGGL(owq_bwd_dww<2>, dim3(rows32, 1), dim3(256), 0, st, da);
+    else hipLaunchKernelGGL(owq_bwd_dww<4>, dim3(rows32, (unsigned)((p.kp32 + 3) / 4)), dim3(256), 0, st, da);
     err = hipGetLastError();
   }
   if (err != hipSuccess) {
