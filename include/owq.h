@@ -275,7 +275,8 @@ typedef struct {
  * (E of the choice) and choice [d_out][G] (i n_hi + j).  G = 1 if group_size == 0, else
  * ceil(d_in / group_size).  One launch on `stream`, no allocation, no synchronisation.
  * Errors: OWQ_ERR_NULL, OWQ_ERR_SHAPE (sizes below 1, d_out G above 2^31 - 1, grid or shrink out
- * of range), OWQ_ERR_BITS, OWQ_ERR_GROUP, OWQ_ERR_INDEX (k out of range), OWQ_ERR_HIP.
+ * of range), OWQ_ERR_BITS, OWQ_ERR_GROUP, OWQ_ERR_INDEX (k out of range), OWQ_ERR_UNSUPPORTED (d_in above
+ * 393216: the weak-column bit mask of a row must fit 48 KiB of LDS), OWQ_ERR_HIP.
  */
 owq_status_t owq_search_config(const owq_search_desc_t *desc, const uint16_t *w, const int32_t *weak_idx,
                                uint16_t *scale, uint16_t *zero, uint8_t *codes, float *err, int32_t *choice,
