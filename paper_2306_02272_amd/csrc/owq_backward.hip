@@ -16,11 +16,11 @@
 // No LDS and no shuffles are needed for the turn.  The zero-point term sum_i a[n, i] z[i] is
 // summed on the vector units beside the matrix instructions and taken off at the end.
 //
-// Three launches per pass of up to 128 tokens (stage dy; product into fp32 partial results per
-// range of rows, the weak columns of dx riding along as one more tile of columns per workgroup;
-// sum of the partial results into fp16 dx), one before them that puts the weak columns in
-// operand order, two more for dww over the whole batch (the activations at the weak columns into
-// operand order, then a product with the tokens on the contraction axis).  A layer with more tiles of weak
+// Three launches per group of up to four passes of 128 tokens (staging: dy into operand order,
+// on the first group also the weak columns and the activations at the weak columns; product into
+// fp32 partial results per range of rows, the weak columns of dx riding along as one more tile of
+// columns per workgroup; sum of the partial results into fp16 dx), one more for dww over the whole
+// batch (a product with the tokens on the contraction axis).  A layer with more tiles of weak
 // columns than block pairs takes a plain kernel for the weak columns of dx instead.
 #include <hip/hip_runtime.h>
 
@@ -63,8 +63,7 @@ struct StageArgs {
 
 // One thread per unit: token 32 m + lane % 32 of the pass, rows 32 rt + 16 s + 4 h + {0..3} and
 // the same + 8 (h = lane / 32): the order in which the turned codes hold their rows.
-__global__ __launch_bounds__(256) void owq_bwd_stage(const StageArgs a) {
-  const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void stage_dy(const StageArgs &a, long long u) {
   const long long per_pass = (long long)a.n_rt * 2 * 4 * 64;
   if (u >= per_pass * a.passes) return;
   const int pass = (int)(u / per_pass);
@@ -108,8 +107,7 @@ struct StageWeakArgs {
 };
 
 // The weak columns in the same operand order: lane % 32 = weak column of the tile, rows as above.
-__global__ __launch_bounds__(256) void owq_bwd_stage_weak(const StageWeakArgs a) {
-  const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void stage_weak(const StageWeakArgs &a, long long u) {
   const long long total = (long long)a.n_rt * 2 * a.kp32 * 64;
   if (u >= total) return;
   const int l = (int)(u & 63);
@@ -411,8 +409,7 @@ struct StageXArgs {
 
 // The activations at the weak columns as A operands with the tokens on the contraction axis:
 // lane % 32 = weak column of the tile, eight consecutive tokens per lane.
-__global__ __launch_bounds__(256) void owq_bwd_stage_x(const StageXArgs a) {
-  const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void stage_x(const StageXArgs &a, long long u) {
   if (u >= (long long)a.steps * a.kp32 * 64) return;
   const int l = (int)(u & 63);
   const long long q = u >> 6;
@@ -432,6 +429,21 @@ __global__ __launch_bounds__(256) void owq_bwd_stage_x(const StageXArgs a) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] = (col >= 0 && 16 * ks + 8 * h + e < a.batch) ? xv[e] : (_Float16)0.f;
   a.xw_st[u] = __builtin_bit_cast(u32x4, v);
+}
+
+struct StageAllArgs {
+  StageArgs dy;
+  StageWeakArgs weak;
+  StageXArgs x;
+  unsigned dy_blocks, weak_blocks;   // blocks [0, dy_blocks) stage dy, the next weak_blocks the weak columns, the rest x
+};
+
+// All staging of a call in one launch: the three parts are independent of each other.
+__global__ __launch_bounds__(256) void owq_bwd_stage_all(const StageAllArgs a) {
+  const unsigned b = blockIdx.x;
+  if (b < a.dy_blocks) stage_dy(a.dy, (long long)b * 256 + threadIdx.x);
+  else if (b < a.dy_blocks + a.weak_blocks) stage_weak(a.weak, (long long)(b - a.dy_blocks) * 256 + threadIdx.x);
+  else stage_x(a.x, (long long)(b - a.dy_blocks - a.weak_blocks) * 256 + threadIdx.x);
 }
 
 struct DwwArgs {
@@ -576,26 +588,30 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
   if ((uintptr_t)workspace & 255u) return OWQ_ERR_BUFFER;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const uint8_t *blob = static_cast<const uint8_t *>(h->dev_buf);
+  uint8_t *ws = static_cast<uint8_t *>(workspace);
   hipError_t err = hipSuccess;
-  if (dx) {
-    u32x4 *a_st = static_cast<u32x4 *>(workspace);
-    float *part = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes);
-    u32x4 *wst = nullptr;
-    float *pw = nullptr;
-    if (p.weak_in_product) {
-      wst = reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes + p.part_bytes);
-      pw = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes + p.part_bytes + p.wst_bytes);
-      StageWeakArgs sw = {reinterpret_cast<const _Float16 *>(blob + g.off_weak_w), wst, g.kp, p.kp32, g.n_rt};
-      const long long wu = (long long)g.n_rt * 2 * p.kp32 * 64;
-      hipLaunchKernelGGL(owq_bwd_stage_weak, dim3((unsigned)((wu + 255) / 256)), dim3(256), 0, st, sw);
-    }
-    const int per_launch = p.passes * kPassTokens;
-    for (int n0 = 0; n0 < batch && err == hipSuccess; n0 += per_launch) {
-      const int ntok = batch - n0 < per_launch ? batch - n0 : per_launch;
-      const int passes = (ntok + kPassTokens - 1) / kPassTokens;
-      StageArgs sa = {static_cast<const _Float16 *>(dy), a_st, g.d_out, g.n_rt, n0, batch, passes};
-      const long long units = (long long)g.n_rt * 512 * passes;
-      hipLaunchKernelGGL(owq_bwd_stage, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, sa);
+  u32x4 *a_st = reinterpret_cast<u32x4 *>(ws);
+  float *part = reinterpret_cast<float *>(ws + p.a_st_bytes);
+  u32x4 *wst = p.weak_in_product ? reinterpret_cast<u32x4 *>(ws + p.a_st_bytes + p.part_bytes) : nullptr;
+  float *pw = p.weak_in_product ? reinterpret_cast<float *>(ws + p.a_st_bytes + p.part_bytes + p.wst_bytes) : nullptr;
+  u32x4 *xw_st = reinterpret_cast<u32x4 *>(ws + p.a_st_bytes + p.part_bytes + p.wst_bytes + p.pw_bytes);
+  const bool want_dww = dww && g.k > 0;
+  const int per_launch = p.passes * kPassTokens;
+  // The first launch stages everything the call needs; later groups of passes stage their dy only.
+  for (int n0 = 0; n0 < batch && err == hipSuccess && (dx || n0 == 0); n0 += per_launch) {
+    const int ntok = batch - n0 < per_launch ? batch - n0 : per_launch;
+    const int passes = (ntok + kPassTokens - 1) / kPassTokens;
+    StageAllArgs sa = {};
+    sa.dy = {static_cast<const _Float16 *>(dy), a_st, g.d_out, g.n_rt, n0, batch, passes};
+    sa.weak = {reinterpret_cast<const _Float16 *>(blob + g.off_weak_w), wst, g.kp, p.kp32, g.n_rt};
+    sa.x = {static_cast<const _Float16 *>(x), reinterpret_cast<const int *>(blob + g.off_weak_idx), xw_st,
+            g.d_in, g.k, p.kp32, batch, p.x_steps};
+    sa.dy_blocks = dx ? (unsigned)(((long long)g.n_rt * 512 * passes + 255) / 256) : 0u;
+    sa.weak_blocks = dx && n0 == 0 && p.weak_in_product ? (unsigned)(((long long)g.n_rt * 2 * p.kp32 * 64 + 255) / 256) : 0u;
+    const unsigned x_blocks = want_dww && n0 == 0 ? (unsigned)(((long long)p.x_steps * p.kp32 * 64 + 255) / 256) : 0u;
+    if (sa.dy_blocks + sa.weak_blocks + x_blocks > 0)
+      hipLaunchKernelGGL(owq_bwd_stage_all, dim3(sa.dy_blocks + sa.weak_blocks + x_blocks), dim3(256), 0, st, sa);
+    if (dx) {
       ProdArgs pa;
       pa.codes = reinterpret_cast<const u32 *>(blob + g.off_codes);
       pa.sz = reinterpret_cast<const u32 *>(blob + g.off_sz);
@@ -629,16 +645,10 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
                        g.d_out, g.d_in, g.kp, n0, ntok};
         hipLaunchKernelGGL(owq_bwd_weak, dim3((unsigned)(g.kp / 8), (unsigned)((ntok + 7) / 8)), dim3(256), 0, st, wa);
       }
-      err = hipGetLastError();
     }
+    err = hipGetLastError();
   }
-  if (dww && g.k > 0 && err == hipSuccess) {
-    u32x4 *xw_st = reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(workspace) + p.a_st_bytes + p.part_bytes +
-                                             p.wst_bytes + p.pw_bytes);
-    StageXArgs sx = {static_cast<const _Float16 *>(x), reinterpret_cast<const int *>(blob + g.off_weak_idx), xw_st,
-                     g.d_in, g.k, p.kp32, batch, p.x_steps};
-    const long long xu = (long long)p.x_steps * p.kp32 * 64;
-    hipLaunchKernelGGL(owq_bwd_stage_x, dim3((unsigned)((xu + 255) / 256)), dim3(256), 0, st, sx);
+  if (want_dww && err == hipSuccess) {
     DwwArgs da = {static_cast<const _Float16 *>(dy), xw_st, dww, g.d_out, g.k, p.kp32, batch, p.x_steps};
     const unsigned rows32 = (unsigned)((g.d_out + 31) / 32);
     if (p.kp32 == 1) hipLaunchKernelGGL(owq_bwd_dww<1>, dim3(rows32, 1), dim3(256), 0, st, da);

@@ -151,6 +151,15 @@ def test_only_one_output_wanted(env):
     check_dww(dww, rdww)
 
 
+def test_dww_of_a_layer_without_weak_columns(env):
+    # k = 0 and only dww wanted: nothing to compute, nothing launched, no error
+    torch, B = env
+    L = make_layer(LayerSpec("k0", 512, 64, 3, 128, 0, 82))
+    x, dy = make_x(L, 3), make_dy(L, 3)
+    dx, dww = run_gpu(env, L, x, dy, want_dx=False)
+    assert dx is None and dww.shape == (64, 0)
+
+
 def test_errors(env):
     torch, B = env
     L = make_layer(LayerSpec("err", 512, 64, 3, 0, 8, 81))
