@@ -57,6 +57,24 @@ def algorithmic_bytes(spec, batch: int, layout: int = 0) -> int:
             + index_bytes + 2 * batch * (spec.d_in + spec.d_out))
 
 
+def pmc_calibration(torch, stream):
+    """A plain copy of known size (reads CALIB_BYTES, writes CALIB_BYTES per launch) for bench_traffic.py."""
+    src = torch.arange(CALIB_BYTES // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1, out=dst)            # an elementwise kernel of torch's own: copy with +1
+    stream.synchronize()
+
+
+def stored_traffic(workload):
+    """HBM bytes per call that bench_traffic.py measured for this workload, or None."""
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        return json.load(open(tpath)).get(workload)
+    except Exception:
+        return None
+
+
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 SEARCH_WORKLOADS = {
     # name: (d_out, d_in, k, bits, group size, grid n_lo x n_hi, shrink, description)
@@ -101,6 +119,8 @@ def bench_search(args) -> int:
                                 err.data_ptr(), 0, raw)
 
     with torch.cuda.stream(stream):
+        if args.pmc_calib:
+            pmc_calibration(torch, stream)
         run(warmup)
         stream.synchronize()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -125,7 +145,7 @@ def bench_search(args) -> int:
         "config": {"workload": desc, "d_out": d_out, "d_in": d_in, "k": k, "group_size": gs, "grid": [n_lo, n_hi],
                    "shrink": shrink, "launch_mode": "eager"},
         "roofline": {"bound": "alu", "achieved": round(tflops, 1), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": stored_traffic(args.workload),
                      "kernel": f"owq_search_kernel<{-(-n_lo * n_hi // 64)}, {0 if gs == 0 or gs > 1024 else -(-gs // 64)}>",
                      "avg_launch_us": round(avg_launch_s * 1e6, 1), "flops_per_launch": flops,
                      "instructions_per_s": round(5 * weights * n_lo * n_hi / avg_launch_s / 1e12, 2)},
@@ -187,6 +207,8 @@ def bench_backward(args) -> int:
                                       ws.data_ptr(), int(ws.numel()), raw)
 
     with torch.cuda.stream(stream):
+        if args.pmc_calib:
+            pmc_calibration(torch, stream)
         run(warmup)
         stream.synchronize()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -213,7 +235,7 @@ def bench_backward(args) -> int:
         "config": {"workload": desc, "batch": batch, "layers": [s.name for s in specs], "launch_mode": "eager"},
         "us_per_call": round(wall_s / calls * 1e6, 3),
         "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": stored_traffic(args.workload),
                      "kernel": f"owq_bwd_product<{specs[0].bits}> (+ stage, sum, weak, dww)",
                      "avg_launch_us": round(avg_call_s * 1e6, 3), "flops_per_launch": flops_step // len(specs)},
     }
@@ -326,13 +348,7 @@ def main() -> int:
 
     with torch.cuda.stream(stream):
         if args.pmc_calib:
-            # a plain copy of known size: reads CALIB_BYTES and writes CALIB_BYTES per launch
-            src = torch.arange(CALIB_BYTES // 4, dtype=torch.int32, device="cuda")
-            dst = torch.empty_like(src)
-            for _ in range(3):
-                torch.add(src, 1, out=dst)            # an elementwise kernel of torch's own: copy with +1
-            stream.synchronize()
-            del src, dst
+            pmc_calibration(torch, stream)
         run_steps(0, args.warmup)
         stream.synchronize()
         graph = None
@@ -366,13 +382,7 @@ def main() -> int:
     launches = args.steps * len(specs)
     avg_launch_s = event_s / launches
     achieved = (step_bytes / len(specs)) / avg_launch_s / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(args.workload)
-        except Exception:
-            traffic = None
+    traffic = stored_traffic(args.workload)
     info = first[0].info()
     flops_per_step = sum(2 * batch * sp.d_out * (sp.d_in + sp.k) for sp in specs)
     small = layout == 1 and batch <= 16 and not args.launch     # the one-launch kernel of the tile layout: bound by the weight stream

@@ -60,7 +60,8 @@ def main():
         for name, vals in ours.items():
             per_call = sum(vals) * 1024.0 * factor / args.calls
             total += per_call
-            lines.append(f"  {name.split('(')[0][:60]:60s} {len(vals):5d} dispatches, {sum(vals) / len(vals):10.1f} KiB each (raw)"
+            short = name.replace("(anonymous namespace)::", "").split("(")[0]
+            lines.append(f"  {short[:60]:60s} {len(vals):5d} dispatches, {sum(vals) / len(vals):10.1f} KiB each (raw)"
                          f" -> {per_call / 1e6:8.3f} MB per call of owq_linear")
     lines.append(f"HBM traffic per call of owq_linear: {total / 1e6:.3f} MB"
                  + (f" (algorithmic {args.algorithmic_bytes / 1e6:.3f} MB, ratio {total / args.algorithmic_bytes:.3f})"

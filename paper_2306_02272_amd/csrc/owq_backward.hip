@@ -62,13 +62,15 @@ struct StageArgs {
 };
 
 // One thread per unit: token 32 m + lane % 32 of the pass, rows 32 rt + 16 s + 4 h + {0..3} and
-// the same + 8 (h = lane / 32): the order in which the turned codes hold their rows.
-__device__ __forceinline__ void stage_dy(const StageArgs &a, long long u) {
-  const long long per_pass = (long long)a.n_rt * 2 * 4 * 64;
-  if (u >= per_pass * a.passes) return;
-  const int pass = (int)(u / per_pass);
-  const long long v0 = u - pass * per_pass;
-  const int l = (int)(v0 & 63), m = (int)((v0 >> 6) & 3), s = (int)((v0 >> 8) & 1), rt = (int)(v0 >> 9);
+// the same + 8 (h = lane / 32): the order in which the turned codes hold their rows.  Block b of
+// the staging takes one tile of 32 tokens and two row tiles: the 64 rows x 2 bytes that its four
+// waves read of a token are one 128-byte line, fetched by this block only.
+__device__ __forceinline__ void stage_dy(const StageArgs &a, unsigned b, int t) {
+  const int pairs = (a.n_rt + 1) >> 1;
+  const int m = (int)(b & 3), pr = (int)((b >> 2) % (unsigned)pairs), pass = (int)((b >> 2) / (unsigned)pairs);
+  const int l = t & 63, s = (t >> 6) & 1, rt = 2 * pr + (t >> 7);
+  if (pass >= a.passes || rt >= a.n_rt) return;
+  const long long u = (long long)pass * a.n_rt * 512 + (((long long)rt * 2 + s) * 4 + m) * 64 + l;
   const int n = a.n0 + kPassTokens * pass + 32 * m + (l & 31), h = l >> 5;
   h8_t v;
   const int ia = 32 * rt + 16 * s + 4 * h;          // rows ia .. ia + 3 and ia + 8 .. ia + 11
@@ -441,7 +443,7 @@ struct StageAllArgs {
 // All staging of a call in one launch: the three parts are independent of each other.
 __global__ __launch_bounds__(256) void owq_bwd_stage_all(const StageAllArgs a) {
   const unsigned b = blockIdx.x;
-  if (b < a.dy_blocks) stage_dy(a.dy, (long long)b * 256 + threadIdx.x);
+  if (b < a.dy_blocks) stage_dy(a.dy, b, (int)threadIdx.x);
   else if (b < a.dy_blocks + a.weak_blocks) stage_weak(a.weak, (long long)(b - a.dy_blocks) * 256 + threadIdx.x);
   else stage_x(a.x, (long long)(b - a.dy_blocks - a.weak_blocks) * 256 + threadIdx.x);
 }
@@ -606,7 +608,7 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
     sa.weak = {reinterpret_cast<const _Float16 *>(blob + g.off_weak_w), wst, g.kp, p.kp32, g.n_rt};
     sa.x = {static_cast<const _Float16 *>(x), reinterpret_cast<const int *>(blob + g.off_weak_idx), xw_st,
             g.d_in, g.k, p.kp32, batch, p.x_steps};
-    sa.dy_blocks = dx ? (unsigned)(((long long)g.n_rt * 512 * passes + 255) / 256) : 0u;
+    sa.dy_blocks = dx ? (unsigned)(((g.n_rt + 1) / 2) * 4 * passes) : 0u;
     sa.weak_blocks = dx && n0 == 0 && p.weak_in_product ? (unsigned)(((long long)g.n_rt * 2 * p.kp32 * 64 + 255) / 256) : 0u;
     const unsigned x_blocks = want_dww && n0 == 0 ? (unsigned)(((long long)p.x_steps * p.kp32 * 64 + 255) / 256) : 0u;
     if (sa.dy_blocks + sa.weak_blocks + x_blocks > 0)
