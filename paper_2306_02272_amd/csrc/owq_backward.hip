@@ -539,10 +539,11 @@ struct BwdPlan {
 
 BwdPlan plan(const owq_layer_info_t &g, int batch) {
   BwdPlan p;
-  // enough workgroups for the chip, few enough ranges that the partial results stay small
+  // one workgroup per compute unit (that is all its registers allow at a time): more ranges of rows would only
+  // add partial results
   const int all_passes = (batch + kPassTokens - 1) / kPassTokens;
   p.passes = all_passes < kLaunchPasses ? (all_passes < 1 ? 1 : all_passes) : kLaunchPasses;
-  int split = (512 + g.nbp * p.passes - 1) / (g.nbp * p.passes);
+  int split = (256 + g.nbp * p.passes - 1) / (g.nbp * p.passes);
   if (split > kSplitMax) split = kSplitMax;
   if (split > g.n_rt) split = g.n_rt;
   if (split < 1) split = 1;
