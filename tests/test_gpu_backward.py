@@ -75,6 +75,7 @@ CASES = [
     ("more_weak_tiles_than_block_pairs", 256, 96, 4, 0, 40, 11),   # the plain kernel for the weak columns of dx
     ("three_weak_tiles", 1024, 128, 3, 128, 70, 35),
     ("six_weak_tiles", 2048, 64, 4, 128, 170, 20),       # dww in two groups of tiles
+    ("two_groups_of_passes", 256, 64, 4, 128, 5, 600),   # more than the 512 tokens one set of launches takes
     ("many_rows", 256, 2048, 3, 128, 4, 40),        # several ranges of rows per block pair
 ]
 
