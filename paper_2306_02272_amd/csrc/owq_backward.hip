@@ -195,21 +195,26 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
 #pragma unroll
   for (int r = 0; r < 16; ++r) wacc[r] = 0.f;
   constexpr int kDw = BITS == 3 ? 3 : 4;                              // dwords of the lane that hold this wave's columns
-  // Everything one row tile needs from memory; the next tile's is fetched while this one is worked on.
+  // What one row tile needs from memory besides its codes; fetched one tile ahead.
   struct Fetched {
-    u32 cw[4];          // codes of K-steps 4 w .. 4 w + 3 of the lane: dwords kDw w .. of its 12 or 16
     u32x4 q[2][2];      // step sizes and zero points of the lane's eight rows of either half
     u32x4 raw[2][4];    // staged dy of the four token tiles
     u32x4 wsu[2];       // staged weak columns
     u32x4 raww[2];      // staged dy of token tile w once more (unscaled operand of the weak product)
   };
-  auto fetch = [&](Fetched &f, int rt) __attribute__((always_inline)) {
+  // codes of K-steps 4 w .. 4 w + 3 of the lane: dwords kDw w .. of its 12 or 16; fetched two tiles ahead
+  struct Codes {
+    u32 cw[4];
+  };
+  auto fetch_codes = [&](Codes &c, int rt) __attribute__((always_inline)) {
     const size_t tile = (size_t)rt * a.nbp + bp;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int dwi = kDw * w + (v < kDw ? v : 0);
-      f.cw[v] = a.codes[((tile * a.chunks + (dwi >> 2)) * 64 + lane) * 4 + (dwi & 3)];
+      c.cw[v] = a.codes[((tile * a.chunks + (dwi >> 2)) * 64 + lane) * 4 + (dwi & 3)];
     }
+  };
+  auto fetch = [&](Fetched &f, int rt) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const int i0 = 32 * rt + 16 * s + 4 * h;
@@ -223,20 +228,22 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
       }
     }
   };
-  auto work = [&](const Fetched &f) __attribute__((always_inline)) {
-    // turned codes of the two column tiles: B operands for both halves of the 32 rows
+  // turned codes of the two column tiles: B operands for both halves of the 32 rows
+  struct Turned {
     u32x4 wb[2][2];
+  };
+  auto turn = [&](const Codes &cd, Turned &o) __attribute__((always_inline)) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       f16_t t;
 #pragma unroll
       for (int r = 0; r < 16; ++r) t[r] = cneg[c];    // start from minus the unpack constant
       if (c == 0) {
-        t = mma(a_operand<BITS, 0>(f.cw, M), sel0, t);
-        t = mma(a_operand<BITS, 1>(f.cw, M), sel1, t);
+        t = mma(a_operand<BITS, 0>(cd.cw, M), sel0, t);
+        t = mma(a_operand<BITS, 1>(cd.cw, M), sel1, t);
       } else {
-        t = mma(a_operand<BITS, 2>(f.cw, M), sel0, t);
-        t = mma(a_operand<BITS, 3>(f.cw, M), sel1, t);
+        t = mma(a_operand<BITS, 2>(cd.cw, M), sel0, t);
+        t = mma(a_operand<BITS, 3>(cd.cw, M), sel1, t);
       }
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
@@ -244,9 +251,11 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
 #pragma unroll
         for (int e = 0; e < 4; ++e)       // small integers: exact whatever the rounding
           pk[e] = __builtin_bit_cast(u32, __builtin_amdgcn_cvt_pkrtz(t[8 * s + 2 * e], t[8 * s + 2 * e + 1]));
-        wb[c][s] = (u32x4){pk[0], pk[1], pk[2], pk[3]};
+        o.wb[c][s] = (u32x4){pk[0], pk[1], pk[2], pk[3]};
       }
     }
+  };
+  auto product = [&](const Fetched &f, const Turned &tw) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const u32x4 q0 = f.q[s][0], q1 = f.q[s][1];
@@ -272,19 +281,30 @@ __global__ __launch_bounds__(kBwdWaves * 64) void owq_bwd_product(const ProdArgs
         }
         const u32x4 av = {ap[0], ap[1], ap[2], ap[3]};
         const h8_t aop = __builtin_bit_cast(h8_t, av);
-        acc[m][0] = mma(aop, __builtin_bit_cast(h8_t, wb[0][s]), acc[m][0]);
-        acc[m][1] = mma(aop, __builtin_bit_cast(h8_t, wb[1][s]), acc[m][1]);
+        acc[m][0] = mma(aop, __builtin_bit_cast(h8_t, tw.wb[0][s]), acc[m][0]);
+        acc[m][1] = mma(aop, __builtin_bit_cast(h8_t, tw.wb[1][s]), acc[m][1]);
       }
     }
   };
-  // the tile after the one being worked on is in flight
+  // Tile t's product runs while tile t + 1's codes are turned (its vector work under the product's
+  // matrix instructions), tile t + 1's operands are in flight and tile t + 2's codes are fetched.
+  const int last = rt1 - 1;
   Fetched cur, nxt;
-  fetch(cur, rt0 < a.n_rt ? rt0 : a.n_rt - 1);
+  Codes c1, c2;
+  Turned tw, tn;
+  fetch_codes(c1, rt0);
+  fetch(cur, rt0);
+  fetch_codes(c2, rt0 + 1 < rt1 ? rt0 + 1 : last);
+  turn(c1, tw);
   for (int rt = rt0; rt < rt1; ++rt) {
-    fetch(nxt, rt + 1 < rt1 ? rt + 1 : rt);          // past the range: this tile again, unused
+    fetch(nxt, rt + 1 < rt1 ? rt + 1 : last);        // past the range: the last tile again, unused
+    c1 = c2;
+    fetch_codes(c2, rt + 2 < rt1 ? rt + 2 : last);
     __builtin_amdgcn_sched_barrier(0);               // the loads above go out before the work below
-    work(cur);
+    product(cur, tw);
+    turn(c1, tn);
     cur = nxt;
+    tw = tn;
   }
   // zero-point term of every token: both halves of the rows, then from the operand layout
   // (token = lane % 32) to the accumulator layout (tokens along the registers)
