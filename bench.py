@@ -66,6 +66,15 @@ def pmc_calibration(torch, stream):
     stream.synchronize()
 
 
+def blas_threads():
+    """Threads the oracle's numpy matrix products use."""
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
+    except Exception:
+        return os.cpu_count() or 1
+
+
 def stored_traffic(workload):
     """HBM bytes per call that bench_traffic.py measured for this workload, or None."""
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -252,7 +261,7 @@ def bench_backward(args) -> int:
             if time.perf_counter() - c0 >= 10.0:
                 break
         c1 = time.perf_counter()
-        result["cpu_baseline"] = {"value": round(reps * nt / 8 / (c1 - c0), 3), "unit": "tokens/s", "cores": 1,
+        result["cpu_baseline"] = {"value": round(reps * nt / 8 / (c1 - c0), 3), "unit": "tokens/s", "cores": blas_threads(),
                                   "kind": "oracle",
                                   "sample": f"{reps} x ({nt} tokens, the first eighth of the output rows of each layer) "
                                             f"in {c1 - c0:.2f} s"}
@@ -427,11 +436,7 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         from oracle import owq_ref
-        try:
-            from threadpoolctl import threadpool_info
-            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            threads = os.cpu_count() or 1
+        threads = blas_threads()
         # a bounded sample of the same step: the first `rows` output rows of every layer (all of
         # them when the step is small), repeated until about ten seconds have gone by
         work = sum(sp.d_out * sp.d_in * batch for sp in specs)
