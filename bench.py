@@ -177,6 +177,8 @@ BACKWARD_WORKLOADS = {
     # name: (index in the list of benchmark configurations, layer indices, tokens, description)
     "backward-opt6.7b-ffn": (2, [0, 1], 512, "backward (dX and dWw, weak-column tuning) of configs[2]'s OPT-6.7B-like FFN "
                                              "pair, 3-bit, group 128, 512 tokens, tile layout"),
+    "backward-llama13b": (3, [0, 1, 2], 512, "backward (dX and dWw, weak-column tuning) of configs[3]'s LLaMA-13B-like q/k/v/o, "
+                                             "gate/up and down projections, 4-bit, group 128, 512 tokens, tile layout"),
 }
 
 

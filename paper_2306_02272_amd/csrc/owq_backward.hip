@@ -559,14 +559,23 @@ struct BwdPlan {
 
 BwdPlan plan(const owq_layer_info_t &g, int batch) {
   BwdPlan p;
-  // one workgroup per compute unit (that is all its registers allow at a time): more ranges of rows would only
-  // add partial results
   const int all_passes = (batch + kPassTokens - 1) / kPassTokens;
   p.passes = all_passes < kLaunchPasses ? (all_passes < 1 ? 1 : all_passes) : kLaunchPasses;
-  int split = (256 + g.nbp * p.passes - 1) / (g.nbp * p.passes);
-  if (split > kSplitMax) split = kSplitMax;
-  if (split > g.n_rt) split = g.n_rt;
-  if (split < 1) split = 1;
+  // Ranges of rows per block pair.  A compute unit holds one workgroup at a time (its registers), so
+  // the product takes rounds of 256 workgroups, each as long as a workgroup's row tiles (plus a fixed
+  // part: set-up and the store of its partial results); every further range costs the sum kernel about
+  // one row tile's time.  Cost in row tiles, fitted to measurements on MI355X.
+  int split = 1;
+  double best = 1e30;
+  for (int sp = 1; sp <= kSplitMax && sp <= g.n_rt; ++sp) {
+    const long long wgs = (long long)g.nbp * sp * p.passes;
+    const double rounds = (double)((wgs + 255) / 256);
+    const double cost = rounds * ((g.n_rt + sp - 1) / sp + 6.0) + 1.1 * sp;
+    if (cost < best) {
+      best = cost;
+      split = sp;
+    }
+  }
   p.rt_per_split = (g.n_rt + split - 1) / split;
   p.split = (g.n_rt + p.rt_per_split - 1) / p.rt_per_split;
   p.a_st_bytes = (size_t)p.passes * g.n_rt * 2 * 4 * 64 * 16;
