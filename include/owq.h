@@ -174,6 +174,32 @@ owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t
 owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream);
 
 /*
+ * owq_linear with the intermediate results of a tile-layout call in caller-owned DEVICE memory
+ * instead of the blob's scratch area: calls on ONE handle may then run on several streams at
+ * once, each with a workspace of its own (the same relaxation of section "Weak Column Tuning"'s
+ * shared dense matrix to concurrent requests).  workspace: 256-byte aligned, at least
+ * owq_workspace_bytes bytes (0 for the other layouts, which need none and ignore it), contents
+ * undefined before and after; calls that share a workspace must not overlap.  Same result as
+ * owq_linear, bit for bit.  Errors as owq_linear, and OWQ_ERR_BUFFER for a workspace that is
+ * too small or misaligned.
+ */
+owq_status_t owq_workspace_bytes(owq_handle_t h, size_t *bytes);
+owq_status_t owq_linear_ws(owq_handle_t h, const void *x, void *y, int32_t batch, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
+ * Measurement aids for benchmarks (the context lines beside the layer's own figures; the paper's
+ * section "Acceleration on Real Device" compares kernel times): owq_probe_read enqueues one
+ * launch that reads `bytes` bytes (a multiple of 16) of DEVICE memory dev_buf (16-byte aligned)
+ * once with 128-bit loads from `workgroups` workgroups of 256 threads and computes nothing;
+ * owq_probe_empty enqueues a launch of 256 workgroups that does nothing.  Errors: OWQ_ERR_NULL,
+ * OWQ_ERR_BUFFER (alignment, size), OWQ_ERR_SHAPE (workgroups out of [1, 65536], 64 GiB or more),
+ * OWQ_ERR_HIP.
+ */
+owq_status_t owq_probe_read(const void *dev_buf, size_t bytes, int32_t workgroups, void *stream);
+owq_status_t owq_probe_empty(void *stream);
+
+/*
  * Weak-column tuning (section "Weak Column Tuning" of the paper: after quantisation only the
  * fp16 weak columns are trained, per task; the low-bit matrix and the weak indices are shared).
  *

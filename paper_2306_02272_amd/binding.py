@@ -28,7 +28,7 @@ OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT = 0, 1, 2
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
            "owq_open_packed", "owq_linear", "owq_free_layer", "owq_layer_info", "owq_export_packed", "owq_set_launch",
            "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_search_config",
-           "owq_backward_workspace_bytes", "owq_linear_backward",
+           "owq_backward_workspace_bytes", "owq_linear_backward", "owq_probe_read", "owq_probe_empty", "owq_workspace_bytes", "owq_linear_ws",
            "owq_status_str"]
 
 
@@ -97,6 +97,10 @@ def lib():
         L.owq_search_config.argtypes = [C.POINTER(SearchDesc), P, P, P, P, P, P, P, P]
         L.owq_backward_workspace_bytes.argtypes = [P, I32, C.POINTER(SZ)]
         L.owq_linear_backward.argtypes = [P, P, P, P, P, I32, P, SZ, P]
+        L.owq_workspace_bytes.argtypes = [P, C.POINTER(SZ)]
+        L.owq_linear_ws.argtypes = [P, P, P, I32, P, SZ, P]
+        L.owq_probe_read.argtypes = [P, SZ, I32, P]
+        L.owq_probe_empty.argtypes = [P]
         for n in EXPORTS:
             getattr(L, n).restype = C.c_int
         L.owq_status_str.argtypes = [C.c_int]
@@ -181,6 +185,26 @@ def owq_open_packed(desc, dev_ptr: int, dev_bytes: int) -> int:
 def owq_linear(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
     _check(lib().owq_linear(C.c_void_p(handle), C.c_void_p(x_ptr), C.c_void_p(y_ptr), batch,
                             C.c_void_p(stream)), "owq_linear")
+
+
+def owq_workspace_bytes(handle: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().owq_workspace_bytes(C.c_void_p(handle), C.byref(n)), "owq_workspace_bytes")
+    return int(n.value)
+
+
+def owq_linear_ws(handle: int, x_ptr: int, y_ptr: int, batch: int, workspace_ptr: int, workspace_bytes: int,
+                  stream: int = 0) -> None:
+    _check(lib().owq_linear_ws(C.c_void_p(handle), C.c_void_p(x_ptr), C.c_void_p(y_ptr), batch,
+                               C.c_void_p(workspace_ptr), workspace_bytes, C.c_void_p(stream)), "owq_linear_ws")
+
+
+def owq_probe_read(dev_ptr: int, nbytes: int, workgroups: int, stream: int = 0) -> None:
+    _check(lib().owq_probe_read(C.c_void_p(dev_ptr), nbytes, workgroups, C.c_void_p(stream)), "owq_probe_read")
+
+
+def owq_probe_empty(stream: int = 0) -> None:
+    _check(lib().owq_probe_empty(C.c_void_p(stream)), "owq_probe_empty")
 
 
 def owq_free_layer(handle: int) -> None:

@@ -168,14 +168,23 @@ owq_status_t owq_open_packed(const owq_layer_desc_t *desc, void *dev_buf, size_t
   return make_handle(g, dev_buf, out);
 }
 
+// Where a tile-layout call keeps its intermediate results: nullptr = the blob's own scratch area
+// with the handle's launch shape; else `mem` of `bytes` bytes with the shape given here.
+struct ScratchChoice {
+  void *mem;
+  uint64_t bytes;
+  int32_t grid, split;
+};
+
 static owq_status_t run_linear(owq_handle_t h, const TaskSets &tasks, const void *x, void *y, int32_t batch,
-                               void *stream) {
+                               void *stream, const ScratchChoice *sc = nullptr) {
   if (batch < 0 || batch > OWQ_MAX_BATCH) return OWQ_ERR_BATCH;
   if (batch == 0) return OWQ_OK;
   if (!x || !y) return OWQ_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(x) % 2 != 0 || reinterpret_cast<uintptr_t>(y) % 2 != 0) return OWQ_ERR_BUFFER;
   const int herr = h->info.layout == OWQ_LAYOUT_TILE
-                       ? launch_tile(h->info, h->dev_buf, h->tile_grid, h->tile_split, h->tile_waves, h->tile_small_split, tasks, x, y, batch, stream)
+                       ? launch_tile(h->info, h->dev_buf, sc ? sc->mem : nullptr, sc ? sc->bytes : 0, sc ? sc->grid : h->tile_grid,
+                                     sc ? sc->split : h->tile_split, h->tile_waves, h->tile_small_split, tasks, x, y, batch, stream)
                        : launch_gemv(h->info, h->shape, h->dev, tasks, x, y, batch, stream);
   if (herr == -2) return OWQ_ERR_SHAPE;     // a launch shape set by the caller does not fit this batch
   if (herr != 0) {
@@ -191,6 +200,24 @@ owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, v
   return run_linear(h, one, x, y, batch, stream);
 }
 
+owq_status_t owq_workspace_bytes(owq_handle_t h, size_t *bytes) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  if (!bytes) return OWQ_ERR_NULL;
+  *bytes = h->info.layout == OWQ_LAYOUT_TILE ? (size_t)tile_scratch(h->info).total : 0;
+  return OWQ_OK;
+}
+
+owq_status_t owq_linear_ws(owq_handle_t h, const void *x, void *y, int32_t batch, void *workspace, size_t workspace_bytes,
+                           void *stream) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  const TaskSets one{nullptr, nullptr, 0};
+  if (h->info.layout != OWQ_LAYOUT_TILE) return run_linear(h, one, x, y, batch, stream);   // needs no workspace
+  if (batch > 0 && !workspace) return OWQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0 || workspace_bytes < tile_scratch(h->info).total) return OWQ_ERR_BUFFER;
+  const ScratchChoice sc{workspace, tile_scratch(h->info).total, h->tile_grid, h->tile_split};
+  return run_linear(h, one, x, y, batch, stream, &sc);
+}
+
 owq_status_t owq_linear_multi(owq_handle_t h, const void *const *weak_sets, int32_t n_sets, const int32_t *task_id,
                               const void *x, void *y, int32_t batch, void *stream) {
   if (!live(h)) return OWQ_ERR_HANDLE;
@@ -201,6 +228,15 @@ owq_status_t owq_linear_multi(owq_handle_t h, const void *const *weak_sets, int3
   const TaskSets tasks{weak_sets, task_id, n_sets};
   return run_linear(h, tasks, x, y, batch, stream);
 }
+
+owq_status_t owq_probe_read(const void *dev_buf, size_t bytes, int32_t workgroups, void *stream) {
+  if (!dev_buf) return OWQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(dev_buf) % 16 != 0 || bytes % 16 != 0) return OWQ_ERR_BUFFER;
+  if (workgroups < 1 || workgroups > 65536 || bytes / 16 > 0xffffffffull) return OWQ_ERR_SHAPE;
+  return launch_read(dev_buf, bytes, workgroups, stream) == 0 ? OWQ_OK : OWQ_ERR_HIP;
+}
+
+owq_status_t owq_probe_empty(void *stream) { return launch_empty(stream) == 0 ? OWQ_OK : OWQ_ERR_HIP; }
 
 owq_status_t owq_weak_set_bytes(owq_handle_t h, size_t *bytes) {
   if (!live(h)) return OWQ_ERR_HANDLE;

@@ -88,18 +88,29 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 // split = 0: the flattened (row group, column step) sequence cut into `grid` equal ranges.
 // small_shape: work split of the one-launch kernel that takes passes of 32 tokens or fewer
 // (0 = the library's choice, -1 = never use that kernel, else S + 100 c, see launch_tile_small).
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, int32_t small_split,
-                const TaskSets &tasks, const void *x, void *y, int32_t batch, void *stream);
+// scratch = DEVICE memory for the intermediate results laid out as tile_scratch() says, of
+// scratch_bytes bytes (at least TileScratch::off_slots plus the slots the grid needs);
+// nullptr = the scratch area inside the blob.
+int launch_tile(const owq_layer_info_t &g, void *blob, void *scratch, uint64_t scratch_bytes, int32_t grid, int32_t split,
+                int32_t waves, int32_t small_split, const TaskSets &tasks, const void *x, void *y, int32_t batch,
+                void *stream);
+
 // The one-launch kernel for 32 tokens or fewer (defined in owq_tile_small.hip).  Returns a
 // hipError_t as int, or -1 when the layer, the split or the alignment of x does not fit it.
-int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, const void *x, void *y, int32_t ntok,
-                      void *stream);
+// part = DEVICE memory of part_bytes bytes for fp32 partial sums when the columns are split.
+int launch_tile_small(const owq_layer_info_t &g, void *blob, void *part, uint64_t part_bytes, int32_t shape, const void *x,
+                      void *y, int32_t ntok, void *stream);
 bool tile_small_split_ok(const owq_layer_info_t &g, int32_t split);
 int prepare_tile_small_kernels();   // LDS opt-in
-void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split);
-int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves);
+// scratch_bytes = size of the scratch memory in use, 0 = the blob's own scratch area
+void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split, uint64_t scratch_bytes = 0);
+int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves, uint64_t scratch_bytes = 0);
 int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit);   // LDS opt-in for grouped layers
 int device_lds_limit(int32_t *bytes);
+
+// Read-only streaming kernels (defined in owq_probe.hip).  Return a hipError_t as int.
+int launch_read(const void *dev, size_t bytes, int32_t workgroups, void *stream);
+int launch_empty(void *stream);
 
 }  // namespace owq
 

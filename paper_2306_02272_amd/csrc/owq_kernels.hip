@@ -304,7 +304,10 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 
   // Only the first two tiles go out ahead of the activations' arrival: more would
   // queue up in front of the set-up's own loads and delay it.
-  constexpr int EARLY = DEPTH < 2 ? DEPTH : 2;
+#ifndef OWQ_EARLY
+#define OWQ_EARLY 2
+#endif
+  constexpr int EARLY = DEPTH < OWQ_EARLY ? DEPTH : OWQ_EARLY;
   set_item(item);                             // waves <= items: every wave has a first item
 #pragma unroll
   for (int d = 0; d < EARLY; ++d) issue(d);

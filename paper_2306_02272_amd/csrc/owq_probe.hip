@@ -1,0 +1,57 @@
+// Measurement aids for the benchmark: the time of a pure 128-bit read of the same bytes a layer
+// kernel streams, and of a launch that does nothing, on the same stream and in the same launch
+// mode as the layer kernels (the context lines beside the layer's own figures).
+#include <hip/hip_runtime.h>
+
+#include "owq_device.h"
+#include "owq_internal.h"
+
+namespace owq {
+
+__device__ u32 g_probe_sink;
+
+// Workgroup b reads 16-byte units [b * per, (b + 1) * per) of p, UNROLL loads of a lane in
+// flight; reads past the slab's end re-read its last unit.
+template <int UNROLL>
+__global__ __launch_bounds__(256) void owq_read_kernel(const u32x4 *p, u32 n16, u32 per) {
+  const u32 lo = blockIdx.x * per;
+  const u32 hi = min(n16, lo + per);
+  if (lo >= hi) return;
+  u32 acc = 0;
+  for (u32 i = lo + threadIdx.x; i < hi; i += 256 * UNROLL) {
+    u32x4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const u32 j = i + (u32)u * 256u;
+      v[u] = __builtin_nontemporal_load(p + (j < hi ? j : hi - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  // keeps the loads alive; the stored value is never read
+  if (acc == 0x9e3779b9u && per == 0xffffffffu) g_probe_sink = acc;
+}
+
+__global__ void owq_empty_kernel(int never) {
+  if (never == 0x7fffffff) g_probe_sink = 1;
+}
+
+// One launch reading `bytes` (a multiple of 16) from dev once with `workgroups` workgroups.
+int launch_read(const void *dev, size_t bytes, int32_t workgroups, void *stream) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return (int)hipSuccess;
+  if (n16 > 0xffffffffull || workgroups < 1) return (int)hipErrorInvalidValue;
+  // slabs of whole 4 KiB pieces (one 16-byte load of every lane of a workgroup)
+  const u32 per = (u32)(((n16 + workgroups - 1) / workgroups + 255) / 256 * 256);
+  const u32 grid = (u32)((n16 + per - 1) / per);
+  hipLaunchKernelGGL(owq_read_kernel<8>, dim3(grid, 1, 1), dim3(256, 1, 1), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4 *>(dev), (u32)n16, per);
+  return (int)hipGetLastError();
+}
+
+int launch_empty(void *stream) {
+  hipLaunchKernelGGL(owq_empty_kernel, dim3(256, 1, 1), dim3(256, 1, 1), 0, static_cast<hipStream_t>(stream), 0);
+  return (int)hipGetLastError();
+}
+
+}  // namespace owq

@@ -628,11 +628,13 @@ int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit) {
 }
 
 // Most workgroups the partial-result slots of the scratch area allow for `waves` per workgroup.
-int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves) {
+int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves, uint64_t scratch_bytes) {
   const TileScratch ts = tile_scratch(g);
+  const uint64_t total = scratch_bytes ? scratch_bytes : ts.total;
+  if (total < ts.off_slots) return 0;
   const int64_t slot = (int64_t)waves * 16384;
   const int64_t n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
-  const int64_t room = (int64_t)(ts.total - ts.off_slots) / slot - n_rg;
+  const int64_t room = (int64_t)(total - ts.off_slots) / slot - n_rg;
   const int64_t steps = n_rg * g.nbp;
   int64_t lim = room < steps ? room : steps;
   const int64_t cap = waves == 8 ? kTileGridMax / 2 : kTileGridMax;
@@ -643,8 +645,8 @@ int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves) {
 // Default work split: ranges aligned to row groups (fewer partial results, and the workgroups
 // of a range use the same activation tile at the same time, which keeps it in L2) unless that
 // costs more than a tenth in steps per workgroup against equal ranges of the whole sequence.
-void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split) {
-  const int32_t limit = tile_grid_limit(g, waves);
+void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split, uint64_t scratch_bytes) {
+  const int32_t limit = tile_grid_limit(g, waves, scratch_bytes);
   int32_t cap = waves == 8 ? kTileGridMax / 2 : kTileGridMax;
   if (g.n_groups > 1 && waves == 4) cap = kTileGridMax / 2;   // grouped layers: one workgroup per compute unit
   if (cap > limit) cap = limit;
@@ -664,15 +666,17 @@ void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid,
   }
 }
 
-int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t split, int32_t waves, int32_t small_split,
-                const TaskSets &tasks, const void *x, void *y, int32_t batch, void *stream) {
+int launch_tile(const owq_layer_info_t &g, void *blob, void *scratch, uint64_t scratch_bytes, int32_t grid, int32_t split,
+                int32_t waves, int32_t small_split, const TaskSets &tasks, const void *x, void *y, int32_t batch,
+                void *stream) {
   const TileScratch ts = tile_scratch(g);
   uint8_t *base = static_cast<uint8_t *>(blob);
-  uint8_t *scr = base + g.off_scratch;
+  uint8_t *scr = scratch ? static_cast<uint8_t *>(scratch) : base + g.off_scratch;
+  const uint64_t scr_bytes = scratch ? scratch_bytes : ts.total;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool grouped = g.n_groups > 1;
   if (waves != 4 && waves != 8) return (int)hipErrorInvalidValue;
-  if (grid < 1 || grid > tile_grid_limit(g, waves)) return (int)hipErrorInvalidValue;
+  if (grid < 1 || grid > tile_grid_limit(g, waves, scr_bytes)) return (int)hipErrorInvalidValue;
   const int n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
   if (split < 0 || split > g.nbp || (split > 0 && grid != n_rg * split)) return (int)hipErrorInvalidValue;
 
@@ -713,7 +717,8 @@ int launch_tile(const owq_layer_info_t &g, void *blob, int32_t grid, int32_t spl
     const int ntok = batch - t0 < kScratchBatch ? batch - t0 : kScratchBatch;
     const int nt = ntok > 32 ? 2 : 1;
     if (ntok <= 32 && small_split >= 0 && tasks.task_id == nullptr) {   // few tokens, one task: one launch
-      const int r = launch_tile_small(g, blob, small_split, xp + (size_t)t0 * g.d_in, yp + (size_t)t0 * g.d_out, ntok, stream);
+      const int r = launch_tile_small(g, blob, scr + ts.off_slots, scr_bytes - ts.off_slots, small_split,
+                                      xp + (size_t)t0 * g.d_in, yp + (size_t)t0 * g.d_out, ntok, stream);
       if (r > 0 || r == -2) return r;
       if (r == 0) continue;
     }

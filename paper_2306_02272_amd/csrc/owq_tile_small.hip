@@ -468,7 +468,7 @@ static int log2_bpg(const owq_layer_info_t &g) {
 // LDS bytes of the kernel for `split` column ranges per row tile, 1 << lg_rt row tiles per
 // workgroup and tokens padded to 1 << lg_tok; 0 = does not fit the kernel's staging (units per
 // thread), the LDS of two workgroups per compute unit or the room for partial sums.
-static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split, int lg_rt, int lg_tok) {
+static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split, int lg_rt, int lg_tok, uint64_t part_bytes) {
   const int nblk = real_blocks(g), lb = log2_bpg(g);
   if (split < 1 || split > nblk || lb < 0) return 0;
   const int rt = 1 << lg_rt, np = 1 << lg_tok;
@@ -481,10 +481,7 @@ static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split, int lg_
   }
   const int nbw_max = base + (rem > 0 ? 1 : 0);
   if (ng_max * rt * 8 > kSmallSzUnits * 256 || nbw_max * np > kSmallXUnits * 16) return 0;
-  if (split > 1) {
-    const TileScratch ts = tile_scratch(g);
-    if ((uint64_t)split * 32 * g.d_out_pad * 4 > ts.total - ts.off_slots) return 0;
-  }
+  if (split > 1 && (uint64_t)split * 32 * g.d_out_pad * 4 > part_bytes) return 0;
   const int xunits = np * ((nbw_max * 16) | 1);
   // activations (or the waves' results), scales, gathered activations, sums per block and token
   const int64_t units = (int64_t)(xunits > kSmallRedUnits ? xunits : kSmallRedUnits) + ng_max * rt * 16 + (int64_t)(g.kp / 8) * np +
@@ -496,8 +493,8 @@ static int32_t small_lds_bytes(const owq_layer_info_t &g, int32_t split, int lg_
 // Work split when the caller does not say: a rough model of the launch in microseconds (a
 // workgroup's fixed cost, the blocks each wave streams, the traffic of activations and of
 // partial sums, the second launch), minimised over the row tiles per workgroup and the ranges.
-static double small_default_shape(const owq_layer_info_t &g, int ntok, int32_t want_split, int want_lg_rt, int32_t *split,
-                                  int *lg_rt) {
+static double small_default_shape(const owq_layer_info_t &g, int ntok, int32_t want_split, int want_lg_rt, uint64_t part_bytes,
+                                  int32_t *split, int *lg_rt) {
   const int nblk = real_blocks(g), lg_tok = log2_ceil(ntok);
   double best = 0.0;
   *split = 0;
@@ -508,7 +505,7 @@ static double small_default_shape(const owq_layer_info_t &g, int ntok, int32_t w
     const int n_rg = (g.n_rt + rt - 1) / rt;
     for (int32_t s = 1; s <= 64 && s <= nblk; ++s) {
       if (want_split > 0 && s != want_split) continue;
-      if (small_lds_bytes(g, s, l, lg_tok) == 0) continue;
+      if (small_lds_bytes(g, s, l, lg_tok, part_bytes) == 0) continue;
       const int64_t wgs = (int64_t)n_rg * s;
       const double rounds = (double)((wgs + 511) / 512);      // 512 places: a few workgroups more cost a whole round
       const int nbw = (nblk + s - 1) / s;
@@ -524,8 +521,9 @@ static double small_default_shape(const owq_layer_info_t &g, int ntok, int32_t w
 
 // owq_set_launch: is this split possible at all (one token, any number of row tiles per workgroup)?
 bool tile_small_split_ok(const owq_layer_info_t &g, int32_t split) {
+  const TileScratch ts = tile_scratch(g);
   for (int l = 0; l <= 2; ++l)
-    if (small_lds_bytes(g, split, l, 0) > 0) return true;
+    if (small_lds_bytes(g, split, l, 0, ts.total - ts.off_slots) > 0) return true;
   return false;
 }
 
@@ -547,14 +545,14 @@ constexpr int kSmallAutoTokens = 16;
 // or 4 of them.  Returns a hipError_t as int, -1 when this layer or the alignment of x does not
 // fit the kernel and the caller has to take the three-launch path, -2 when the caller asked
 // for a shape that does not fit this number of tokens.
-int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, const void *x, void *y, int32_t ntok,
-                      void *stream) {
+int launch_tile_small(const owq_layer_info_t &g, void *blob, void *part, uint64_t part_bytes, int32_t shape, const void *x,
+                      void *y, int32_t ntok, void *stream) {
   if (ntok < 1 || ntok > 32 || shape < 0 || (shape == 0 && ntok > kSmallAutoTokens)) return -1;
   if ((reinterpret_cast<uintptr_t>(x) & 15) != 0 || g.d_in % kBlockCols != 0) return -1;   // whole blocks, aligned rows
   if (log2_bpg(g) < 0) return -1;                                                            // groups of 2^n blocks
   int32_t split = 0;
   int lg_rt = 0;
-  const double cost = small_default_shape(g, ntok, shape % 100, shape / 100 - 1, &split, &lg_rt);
+  const double cost = small_default_shape(g, ntok, shape % 100, shape / 100 - 1, part_bytes, &split, &lg_rt);
   if (split < 1) return shape > 0 ? -2 : -1;
   if (shape == 0) {
     // Large layers stream so many blocks per wave that the three launches do as well or better: their
@@ -563,7 +561,6 @@ int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, cons
     if (cost * 1.15 >= 15.0 + code_mb / 4.2) return -1;
   }
   const int lg_tok = log2_ceil(ntok);
-  const TileScratch ts = tile_scratch(g);
   uint8_t *base = static_cast<uint8_t *>(blob);
   SmallArgs a;
   a.codes = reinterpret_cast<const u32x4 *>(base + g.off_codes);
@@ -573,7 +570,7 @@ int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, cons
   a.weak_w = reinterpret_cast<const u32x4 *>(base + g.off_weak_w);
   a.x = static_cast<const _Float16 *>(x);
   a.y = static_cast<_Float16 *>(y);
-  a.part = reinterpret_cast<float *>(base + g.off_scratch + ts.off_slots);
+  a.part = static_cast<float *>(part);
   a.d_in = g.d_in; a.d_out = g.d_out; a.d_out_pad = g.d_out_pad; a.n_rt = g.n_rt; a.ntok = ntok; a.nbp = g.nbp;
   const int nblk = real_blocks(g);
   a.blk_base = nblk / split; a.blk_rem = nblk % split;
@@ -582,7 +579,7 @@ int launch_tile_small(const owq_layer_info_t &g, void *blob, int32_t shape, cons
   const int n_rg = (g.n_rt + (1 << lg_rt) - 1) >> lg_rt;
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(pick_small(g.bits), dim3((unsigned)split, (unsigned)n_rg, 1), dim3(256, 1, 1),
-                     (size_t)small_lds_bytes(g, split, lg_rt, lg_tok), st, a);
+                     (size_t)small_lds_bytes(g, split, lg_rt, lg_tok, part_bytes), st, a);
   if (split > 1)
     hipLaunchKernelGGL(owq_tile_small_sum, dim3((unsigned)((g.d_out + 255) / 256), (unsigned)ntok, 1), dim3(256, 1, 1), 0, st,
                        a.part, a.y, split, ntok, g.d_out, g.d_out_pad);
