@@ -46,12 +46,14 @@ typedef enum {
   OWQ_ERR_HANDLE = 9,     /* not a live handle */
   OWQ_ERR_HIP = 10,       /* a HIP call failed; see owq_layer_info_t.last_hip_error */
   OWQ_ERR_UNSUPPORTED = 11, /* the layer needs more on-chip memory than one workgroup may use */
-  OWQ_ERR_LAYOUT = 12      /* layout is none of OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT */
+  OWQ_ERR_LAYOUT = 12,     /* layout is none of OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT */
+  OWQ_ERR_SCRATCH = 13     /* owq_linear_static: the layer needs more than OWQ_STATIC_SCRATCH_BYTES of scratch memory */
 } owq_status_t;
 
 #define OWQ_MAX_BATCH 65535
 #define OWQ_MAX_WEAK_SETS 65536
 #define OWQ_FORMAT_VERSION 1
+#define OWQ_STATIC_SCRATCH_BYTES (32u << 20) /* the library's own scratch array, one per GPU, see owq_linear_static */
 
 /*
  * Plain description of a layer.  Every pointer is HOST memory, borrowed for the
@@ -186,6 +188,22 @@ owq_status_t owq_linear(owq_handle_t h, const void *x, void *y, int32_t batch, v
 owq_status_t owq_workspace_bytes(owq_handle_t h, size_t *bytes);
 owq_status_t owq_linear_ws(owq_handle_t h, const void *x, void *y, int32_t batch, void *workspace, size_t workspace_bytes,
                            void *stream);
+
+/*
+ * owq_linear for callers that cannot allocate and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The intermediate
+ * results of a tile-layout call go to a static DEVICE array inside the library, of
+ * OWQ_STATIC_SCRATCH_BYTES bytes, one per GPU, held from the library's load until the process
+ * ends; the blob is only read.  The call allocates nothing and frees nothing.  The work is split
+ * so that its partial results fit the array (fewer workgroups than owq_linear may use for large
+ * layers); the result equals owq_linear's to rounding (the order of the partial sums may
+ * differ).  A layer whose staged activations and one partial result per 256 rows do not fit the
+ * array is rejected with OWQ_ERR_SCRATCH.  Every call on a GPU shares that GPU's array and
+ * finds the previous call's contents in it (nothing in it has to start at zero: every kernel
+ * writes what it later reads); calls that overlap in time on one GPU race.  Handles of the
+ * other layouts use no scratch memory and run as owq_linear does.
+ */
+owq_status_t owq_linear_static(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream);
 
 /*
  * Measurement aids for benchmarks (the context lines beside the layer's own figures; the paper's

@@ -18,17 +18,18 @@ LIB_PATH = os.path.join(_HERE, "libowq.so")
 OWQ_OK = 0
 STATUS_NAMES = ["OWQ_OK", "OWQ_ERR_NULL", "OWQ_ERR_SHAPE", "OWQ_ERR_BITS", "OWQ_ERR_GROUP",
                 "OWQ_ERR_CODE_RANGE", "OWQ_ERR_INDEX", "OWQ_ERR_BUFFER", "OWQ_ERR_BATCH",
-                "OWQ_ERR_HANDLE", "OWQ_ERR_HIP", "OWQ_ERR_UNSUPPORTED", "OWQ_ERR_LAYOUT"]
+                "OWQ_ERR_HANDLE", "OWQ_ERR_HIP", "OWQ_ERR_UNSUPPORTED", "OWQ_ERR_LAYOUT", "OWQ_ERR_SCRATCH"]
 (OWQ_ERR_NULL, OWQ_ERR_SHAPE, OWQ_ERR_BITS, OWQ_ERR_GROUP, OWQ_ERR_CODE_RANGE, OWQ_ERR_INDEX,
  OWQ_ERR_BUFFER, OWQ_ERR_BATCH, OWQ_ERR_HANDLE, OWQ_ERR_HIP, OWQ_ERR_UNSUPPORTED,
- OWQ_ERR_LAYOUT) = range(1, 13)
+ OWQ_ERR_LAYOUT, OWQ_ERR_SCRATCH) = range(1, 14)
+OWQ_STATIC_SCRATCH_BYTES = 32 << 20
 OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT = 0, 1, 2
 
 # every symbol include/owq.h declares
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
            "owq_open_packed", "owq_linear", "owq_free_layer", "owq_layer_info", "owq_export_packed", "owq_set_launch",
            "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_search_config",
-           "owq_backward_workspace_bytes", "owq_linear_backward", "owq_probe_read", "owq_probe_empty", "owq_workspace_bytes", "owq_linear_ws",
+           "owq_backward_workspace_bytes", "owq_linear_backward", "owq_probe_read", "owq_probe_empty", "owq_workspace_bytes", "owq_linear_ws", "owq_linear_static",
            "owq_status_str"]
 
 
@@ -99,6 +100,7 @@ def lib():
         L.owq_linear_backward.argtypes = [P, P, P, P, P, I32, P, SZ, P]
         L.owq_workspace_bytes.argtypes = [P, C.POINTER(SZ)]
         L.owq_linear_ws.argtypes = [P, P, P, I32, P, SZ, P]
+        L.owq_linear_static.argtypes = [P, P, P, I32, P]
         L.owq_probe_read.argtypes = [P, SZ, I32, P]
         L.owq_probe_empty.argtypes = [P]
         for n in EXPORTS:
@@ -197,6 +199,11 @@ def owq_linear_ws(handle: int, x_ptr: int, y_ptr: int, batch: int, workspace_ptr
                   stream: int = 0) -> None:
     _check(lib().owq_linear_ws(C.c_void_p(handle), C.c_void_p(x_ptr), C.c_void_p(y_ptr), batch,
                                C.c_void_p(workspace_ptr), workspace_bytes, C.c_void_p(stream)), "owq_linear_ws")
+
+
+def owq_linear_static(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: int = 0) -> None:
+    _check(lib().owq_linear_static(C.c_void_p(handle), C.c_void_p(x_ptr), C.c_void_p(y_ptr), batch,
+                                   C.c_void_p(stream)), "owq_linear_static")
 
 
 def owq_probe_read(dev_ptr: int, nbytes: int, workgroups: int, stream: int = 0) -> None:

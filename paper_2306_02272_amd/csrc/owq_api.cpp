@@ -218,6 +218,22 @@ owq_status_t owq_linear_ws(owq_handle_t h, const void *x, void *y, int32_t batch
   return run_linear(h, one, x, y, batch, stream, &sc);
 }
 
+owq_status_t owq_linear_static(owq_handle_t h, const void *x, void *y, int32_t batch, void *stream) {
+  if (!live(h)) return OWQ_ERR_HANDLE;
+  const TaskSets one{nullptr, nullptr, 0};
+  if (h->info.layout != OWQ_LAYOUT_TILE) return run_linear(h, one, x, y, batch, stream);   // needs no scratch memory
+  ScratchChoice sc{nullptr, OWQ_STATIC_SCRATCH_BYTES, 0, 0};
+  // the work split that fits the array: fewer partial-result slots than the blob's own area may hold
+  tile_default_shape(h->info, h->tile_waves, &sc.grid, &sc.split, sc.bytes);
+  if (sc.grid < 1) return OWQ_ERR_SCRATCH;
+  const int herr = static_scratch(&sc.mem);
+  if (herr != 0) {
+    h->info.last_hip_error = herr;
+    return OWQ_ERR_HIP;
+  }
+  return run_linear(h, one, x, y, batch, stream, &sc);
+}
+
 owq_status_t owq_linear_multi(owq_handle_t h, const void *const *weak_sets, int32_t n_sets, const int32_t *task_id,
                               const void *x, void *y, int32_t batch, void *stream) {
   if (!live(h)) return OWQ_ERR_HANDLE;
@@ -370,6 +386,7 @@ const char *owq_status_str(owq_status_t s) {
     case OWQ_ERR_HIP: return "HIP call failed";
     case OWQ_ERR_UNSUPPORTED: return "layer too large for one workgroup's on-chip memory";
     case OWQ_ERR_LAYOUT: return "unknown layout";
+    case OWQ_ERR_SCRATCH: return "the layer needs more scratch memory than the library's static array holds";
   }
   return "unknown status";
 }

@@ -94,7 +94,9 @@ int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when n
 int launch_tile(const owq_layer_info_t &g, void *blob, void *scratch, uint64_t scratch_bytes, int32_t grid, int32_t split,
                 int32_t waves, int32_t small_split, const TaskSets &tasks, const void *x, void *y, int32_t batch,
                 void *stream);
-
+// Device address of the library's static scratch array on the current device (looked up once
+// per device).  Returns a hipError_t as int.
+int static_scratch(void **ptr);
 // The one-launch kernel for 32 tokens or fewer (defined in owq_tile_small.hip).  Returns a
 // hipError_t as int, or -1 when the layer, the split or the alignment of x does not fit it.
 // part = DEVICE memory of part_bytes bytes for fp32 partial sums when the columns are split.

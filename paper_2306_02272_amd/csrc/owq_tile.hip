@@ -26,6 +26,8 @@
 // No atomics: results are reproducible.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include <type_traits>
 
 #include "owq_internal.h"
@@ -737,6 +739,32 @@ int launch_tile(const owq_layer_info_t &g, void *blob, void *scratch, uint64_t s
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
+  return (int)hipSuccess;
+}
+
+// The library's own scratch memory for callers that can pass no workspace and whose blobs may
+// not be written to: one array per GPU, held until the process ends.  The symbol below is a
+// host-side stand-in; its device address is looked up once per device (hipGetSymbolAddress)
+// and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char g_static_scratch[OWQ_STATIC_SCRATCH_BYTES];
+
+int static_scratch(void **ptr) {
+  constexpr int kMaxDevices = 64;
+  static void *addr[kMaxDevices];
+  static std::mutex lock;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!addr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
   return (int)hipSuccess;
 }
 
