@@ -62,14 +62,6 @@ constexpr int kSmallRedUnits = 1024;  // LDS units of the waves' results: [4][16
 constexpr int kSmallGather = 8;       // gathered activations a thread fetches at once: 2048 (weak column, token) pairs
 constexpr int kSmallLdsMax = 80 * 1024;   // two workgroups per compute unit
 
-// Developer aid (build with -DOWQ_TRACE): per-wave time stamps of the kernel's phases.
-#ifdef OWQ_TRACE
-__device__ long long g_trace_small[4096 * 8];
-#define STRACE(slot) do { if (lane == 0) g_trace_small[(((blockIdx.y * gridDim.x + blockIdx.x) * kSmallWaves + w) & 4095) * 8 + (slot)] = (long long)wall_clock64(); } while (0)
-#else
-#define STRACE(slot) do { } while (0)
-#endif
-
 // grid (column ranges, groups of row tiles).  Layers with one scale per row run as one group of
 // scales that spans all blocks.
 template <int BITS>
@@ -81,7 +73,6 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, kg = lane >> 5;
-  STRACE(0);
   const int RT = 1 << a.lg_rt, KS = kSmallWaves >> a.lg_rt;
   const int rtl = w & (RT - 1), ks = w >> a.lg_rt;
   const int sp = blockIdx.x, rg = blockIdx.y;
@@ -179,7 +170,6 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
     wa[i] = a.weak_w[(u32)((rt * 32 + n) * kunits + (u < kunits ? u : 0))];
   }
   __builtin_amdgcn_sched_barrier(0);         // all of these are in flight before anything waits
-  STRACE(1);
 
   // ---- (2) the gathers go out once their indices are there; scales and activations into LDS ---
   // The gathered values stay in registers until the wave's blocks are done: nothing waits for them.
@@ -255,9 +245,7 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
       __builtin_amdgcn_sched_barrier(0);     // one unit at a time: interleaving them costs registers, not time
     }
   }
-  STRACE(2);
   __syncthreads();
-  STRACE(3);
 
   // ---- (3) the wave's blocks ------------------------------------------------------------
   Magic M;
@@ -349,7 +337,6 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
   if (b > wb0) {                               // the last block's scaling
     if ((b - 1 - wb0) & 1) scale_in(acc1, gi_prev); else scale_in(acc0, gi_prev);
   }
-  STRACE(4);
 
   // ---- (4) weak columns -----------------------------------------------------------------
   // element (weak column t, token) -> unit t >> 3 of the token, half t & 7
@@ -379,7 +366,6 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
       if (t < a.kp) xw_h[(((t >> 3) << a.lg_tok) + tok) * 8 + (t & 7)] = j2[i] ? (unsigned short)v2[i] : (unsigned short)0;
     }
   }
-  STRACE(5);
   __syncthreads();        // every wave is past its blocks: the room of the activations is free for the results
   if (kunits > 0) {
     const u32x4 z4 = {0u, 0u, 0u, 0u};
@@ -402,7 +388,6 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
       tot = mma(__builtin_bit_cast(h8_t, uv ? av : z4), __builtin_bit_cast(h8_t, uv ? bv : z4), tot);
     }
   }
-  STRACE(6);
 
   // ---- (5) the results of the waves of a row tile, added in a fixed order ----------------
 #pragma unroll
@@ -420,7 +405,6 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
       a.part[(size_t)(sp * a.ntok + nn) * a.d_out_pad + grow] = v;
     }
   }
-  STRACE(7);
 }
 
 // Adds the results of the column ranges of every row (fixed order) and rounds to fp16.
@@ -587,9 +571,3 @@ int launch_tile_small(const owq_layer_info_t &g, void *blob, void *part, uint64_
 }
 
 }  // namespace owq
-
-#ifdef OWQ_TRACE
-extern "C" int owq_debug_read_trace_small(long long *host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(owq::g_trace_small), sizeof(long long) * 4096 * 8);
-}
-#endif
