@@ -320,7 +320,7 @@ typedef struct {
  * ceil(d_in / group_size).  One launch on `stream`, no allocation, no synchronisation.
  * Errors: OWQ_ERR_NULL, OWQ_ERR_SHAPE (sizes below 1, d_out G above 2^31 - 1, grid or shrink out
  * of range), OWQ_ERR_BITS, OWQ_ERR_GROUP, OWQ_ERR_INDEX (k out of range), OWQ_ERR_UNSUPPORTED (d_in above
- * 393216: the weak-column bit mask of a row must fit 48 KiB of LDS), OWQ_ERR_HIP.
+ * 385024: the weak-column bit mask of a row must fit 47 KiB of LDS), OWQ_ERR_HIP.
  */
 owq_status_t owq_search_config(const owq_search_desc_t *desc, const uint16_t *w, const int32_t *weak_idx,
                                uint16_t *scale, uint16_t *zero, uint8_t *codes, float *err, int32_t *choice,
@@ -342,9 +342,13 @@ owq_status_t owq_search_config(const owq_search_desc_t *desc, const uint16_t *w,
  * is NULL), dx fp16 [batch][d_in] (written; NULL = not wanted), dww fp32 [d_out][k] (written,
  * summed over the whole batch; NULL = not wanted), workspace of at least
  * owq_backward_workspace_bytes bytes for this batch, 256-byte aligned (contents undefined before and after;
- * calls that share a workspace must not overlap).  fp32 accumulation; dy times the step size
- * is rounded to fp16 once before the product (relative 2^-11 per term); dx is rounded to fp16
- * once.  Work is queued on `stream`, nothing is allocated, nothing synchronises.
+ * calls that share a workspace must not overlap).  fp32 accumulation; dy is first scaled by the
+ * power of two that brings its largest magnitude into [512, 1024) (exact, undone on the sums), then
+ * dy times the step size is rounded to fp16 once before the product: relative 2^-11 per term whatever
+ * the magnitude of the gradients, except for terms whose scaled product falls below 2^-14 (with step
+ * sizes of 1e-3: dy more than ten thousand times smaller than the largest one), whose absolute error
+ * stays below 2^-25, against largest terms of about 1; step sizes above 64 may overflow the product;
+ * dx is rounded to fp16 once.  Work is queued on `stream`, nothing is allocated, nothing synchronises.
  * Errors: OWQ_ERR_HANDLE, OWQ_ERR_LAYOUT, OWQ_ERR_NULL, OWQ_ERR_BATCH, OWQ_ERR_BUFFER (workspace
  * too small, a pointer misaligned), OWQ_ERR_HIP.  batch == 0 is a no-op.
  */

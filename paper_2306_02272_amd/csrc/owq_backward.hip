@@ -36,6 +36,7 @@ constexpr int kPassTokens = 128;     // tokens per pass: four accumulator tiles 
 constexpr int kBwdWaves = 4;         // one per quarter of a tile's 256 columns
 constexpr int kSplitMax = 16;        // most ranges of rows per block pair
 constexpr int kLaunchPasses = 4;     // passes (of 128 tokens) that one set of launches takes
+constexpr size_t kScanBytes = 2048;  // end of the workspace: the magnitude scan's 256 words, then the exponent
 
 // bit offset of the pair of codes that column c (0..15) of K-step t holds, as in the packer
 __device__ const signed char kPairOffset3[4][4] = {{0, 3, 6, 1}, {4, 7, 2, 5}, {0, 3, 6, 1}, {4, 7, 4, 7}};
@@ -55,10 +56,43 @@ __device__ __forceinline__ void load_h(const _Float16 *const (&p)[N], _Float16 (
   for (int e = 0; e < N; ++e) out[e] = __builtin_bit_cast(_Float16, (unsigned short)r[e]);
 }
 
+constexpr int kMaxBlocks = 256;      // workgroups of the magnitude scan = entries of its result
+
+// Largest magnitude of dy, as fp16 bit patterns without sign (Inf and NaN count as the largest
+// finite number): one entry per workgroup, no atomics.  The product forms dy * s in fp16; with
+// gradients of 1e-3 and step sizes of 1e-3 that product is a subnormal number and loses most of
+// its bits, so dy is first scaled by a power of two (exact) that brings its largest magnitude
+// into [512, 1024), and the sums are scaled back at the end (also exact).
+__global__ __launch_bounds__(256) void owq_bwd_absmax(const u32x4 *dy, size_t n16, size_t n_halves, const unsigned short *dy_h,
+                                                      u32 *out) {
+  __shared__ u32 red[4];
+  u32 m = 0;
+  auto take = [&](u32 w) {
+    const u32 lo = w & 0x7fffu, hi = (w >> 16) & 0x7fffu;
+    m = max(m, max(lo, hi));
+  };
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)kMaxBlocks * 256) {
+    const u32x4 v = dy[i];
+    take(v.x); take(v.y); take(v.z); take(v.w);
+  }
+  for (size_t i = n16 * 8 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n_halves; i += (size_t)kMaxBlocks * 256)
+    take(dy_h[i]);
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) m = max(m, (u32)__shfl_xor((int)m, d));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) out[blockIdx.x] = min(max(max(red[0], red[1]), max(red[2], red[3])), 0x7bffu);
+}
+
+// The power of two dy is scaled by: 2^k brings the largest magnitude into [2^9, 2^10).
+__device__ __forceinline__ int scale_exponent(u32 max_bits) { return 24 - (int)(max_bits >> 10); }
+
 struct StageArgs {
   const _Float16 *dy;   // [batch][d_out]
   u32x4 *a_st;          // [pass][n_rt][2][4 token tiles][64 lanes] units of 8 fp16
   int d_out, n_rt, n0, batch, passes;
+  const u32 *maxima;    // [kMaxBlocks] from owq_bwd_absmax
+  int *kword;           // the exponent, for the kernel that scales the sums back
 };
 
 // One thread per unit: token 32 m + lane % 32 of the pass, rows 32 rt + 16 s + 4 h + {0..3} and
@@ -66,6 +100,16 @@ struct StageArgs {
 // the staging takes one tile of 32 tokens and two row tiles: the 64 rows x 2 bytes that its four
 // waves read of a token are one 128-byte line, fetched by this block only.
 __device__ __forceinline__ void stage_dy(const StageArgs &a, unsigned b, int t) {
+  // the scale: every workgroup reduces the scan's 256 entries again (cheaper than one more launch)
+  __shared__ u32 red[4];
+  u32 mx = a.maxima[t];
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) mx = max(mx, (u32)__shfl_xor((int)mx, d));
+  if ((t & 63) == 0) red[t >> 6] = mx;
+  __syncthreads();
+  const int kexp = scale_exponent(max(max(red[0], red[1]), max(red[2], red[3])));
+  const float scale = __builtin_ldexpf(1.0f, kexp);
+  if (b == 0 && t == 0) *a.kword = kexp;
   const int pairs = (a.n_rt + 1) >> 1;
   const int m = (int)(b & 3), pr = (int)((b >> 2) % (unsigned)pairs), pass = (int)((b >> 2) / (unsigned)pairs);
   const int l = t & 63, s = (t >> 6) & 1, rt = 2 * pr + (t >> 7);
@@ -99,6 +143,8 @@ __device__ __forceinline__ void stage_dy(const StageArgs &a, unsigned b, int t) 
       v[e] = (n < a.batch && i < a.d_out) ? x[e] : (_Float16)0.f;
     }
   }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (_Float16)((float)v[e] * scale);      // a power of two, below 1024 afterwards: exact
   a.a_st[u] = __builtin_bit_cast(u32x4, v);
 }
 
@@ -345,6 +391,7 @@ struct SumArgs {
   const int *weak_idx;
   _Float16 *dx;         // [batch][d_in]
   int d_in, d_in_pad, split, n0, ntok, k, kp32, dense_blocks;
+  const int *kword;     // dy was scaled by 2^*kword
 };
 
 // dx: the partial results added in a fixed order.  Blocks below dense_blocks take 1024 columns
@@ -353,6 +400,7 @@ __global__ __launch_bounds__(256) void owq_bwd_sum(const SumArgs a) {
   if ((int)blockIdx.y >= a.ntok) return;
   const int pass = blockIdx.y / kPassTokens, nl = blockIdx.y % kPassTokens;
   const size_t base = (size_t)pass * a.split * kPassTokens;           // first (range, token) row of this pass
+  const float back = __builtin_ldexpf(1.0f, -*a.kword);                // undo the scaling of dy
   if ((int)blockIdx.x < a.dense_blocks) {
     const int j = (blockIdx.x * 256 + threadIdx.x) * 4;            // four columns per thread (d_in_pad is a multiple of 256)
     if (j >= a.d_in) return;
@@ -363,7 +411,7 @@ __global__ __launch_bounds__(256) void owq_bwd_sum(const SumArgs a) {
     _Float16 *out = a.dx + (size_t)(a.n0 + blockIdx.y) * a.d_in + j;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-      if (j + e < a.d_in && !((weak >> e) & 1u)) out[e] = (_Float16)v[e];
+      if (j + e < a.d_in && !((weak >> e) & 1u)) out[e] = (_Float16)(v[e] * back);
   } else {
     const int t = ((int)blockIdx.x - a.dense_blocks) * 256 + threadIdx.x;
     if (a.pw == nullptr || t >= a.k) return;
@@ -371,7 +419,7 @@ __global__ __launch_bounds__(256) void owq_bwd_sum(const SumArgs a) {
     if ((unsigned)col >= (unsigned)a.d_in) return;
     float v = 0.f;
     for (int s = 0; s < a.split; ++s) v += a.pw[(base + (size_t)s * kPassTokens + nl) * (32 * a.kp32) + t];
-    a.dx[(size_t)(a.n0 + blockIdx.y) * a.d_in + col] = (_Float16)v;
+    a.dx[(size_t)(a.n0 + blockIdx.y) * a.d_in + col] = (_Float16)(v * back);
   }
 }
 
@@ -586,7 +634,7 @@ BwdPlan plan(const owq_layer_info_t &g, int batch) {
   p.pw_bytes = p.weak_in_product ? (size_t)p.passes * p.split * kPassTokens * 32 * p.kp32 * 4 : 0;
   p.x_steps = (batch + 15) / 16;
   p.xw_bytes = g.k > 0 ? (size_t)p.x_steps * p.kp32 * 64 * 16 : 0;
-  p.total = p.a_st_bytes + p.part_bytes + p.wst_bytes + p.pw_bytes + p.xw_bytes;
+  p.total = p.a_st_bytes + p.part_bytes + p.wst_bytes + p.pw_bytes + p.xw_bytes + kScanBytes;
   return p;
 }
 
@@ -627,14 +675,21 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
   u32x4 *wst = p.weak_in_product ? reinterpret_cast<u32x4 *>(ws + p.a_st_bytes + p.part_bytes) : nullptr;
   float *pw = p.weak_in_product ? reinterpret_cast<float *>(ws + p.a_st_bytes + p.part_bytes + p.wst_bytes) : nullptr;
   u32x4 *xw_st = reinterpret_cast<u32x4 *>(ws + p.a_st_bytes + p.part_bytes + p.wst_bytes + p.pw_bytes);
+  u32 *maxima = reinterpret_cast<u32 *>(ws + p.total - kScanBytes);
+  int *kword = reinterpret_cast<int *>(maxima + kMaxBlocks);
   const bool want_dww = dww && g.k > 0;
   const int per_launch = p.passes * kPassTokens;
+  if (dx) {
+    const size_t halves = (size_t)batch * g.d_out;
+    hipLaunchKernelGGL(owq_bwd_absmax, dim3(kMaxBlocks), dim3(256), 0, st, static_cast<const u32x4 *>(dy), halves / 8, halves,
+                       static_cast<const unsigned short *>(dy), maxima);
+  }
   // The first launch stages everything the call needs; later groups of passes stage their dy only.
   for (int n0 = 0; n0 < batch && err == hipSuccess && (dx || n0 == 0); n0 += per_launch) {
     const int ntok = batch - n0 < per_launch ? batch - n0 : per_launch;
     const int passes = (ntok + kPassTokens - 1) / kPassTokens;
     StageAllArgs sa = {};
-    sa.dy = {static_cast<const _Float16 *>(dy), a_st, g.d_out, g.n_rt, n0, batch, passes};
+    sa.dy = {static_cast<const _Float16 *>(dy), a_st, g.d_out, g.n_rt, n0, batch, passes, maxima, kword};
     sa.weak = {reinterpret_cast<const _Float16 *>(blob + g.off_weak_w), wst, g.kp, p.kp32, g.n_rt};
     sa.x = {static_cast<const _Float16 *>(x), reinterpret_cast<const int *>(blob + g.off_weak_idx), xw_st,
             g.d_in, g.k, p.kp32, batch, p.x_steps};
@@ -669,7 +724,7 @@ extern "C" owq_status_t owq_linear_backward(owq_handle_t h, const void *dy, cons
       else hipLaunchKernelGGL((owq_bwd_product<4, false>), grid, block, 0, st, pa);
       const int dense_blocks = (g.d_in + 1023) / 1024, weak_blocks = p.weak_in_product ? (g.k + 255) / 256 : 0;
       SumArgs su = {part, pw, blob + g.off_wmask, reinterpret_cast<const int *>(blob + g.off_weak_idx),
-                    static_cast<_Float16 *>(dx), g.d_in, g.nbp * 256, p.split, n0, ntok, g.k, p.kp32, dense_blocks};
+                    static_cast<_Float16 *>(dx), g.d_in, g.nbp * 256, p.split, n0, ntok, g.k, p.kp32, dense_blocks, kword};
       hipLaunchKernelGGL(owq_bwd_sum, dim3((unsigned)(dense_blocks + weak_blocks), (unsigned)ntok), dim3(256), 0, st, su);
       if (g.k > 0 && !p.weak_in_product) {
         WeakArgs wa = {static_cast<const _Float16 *>(dy), reinterpret_cast<const _Float16 *>(blob + g.off_weak_w),

@@ -95,6 +95,27 @@ def test_backward_matches_oracle(env, case):
         assert rel <= REL_L2, (name, rel)
 
 
+@pytest.mark.parametrize("sigma", [1.0, 1e-3, 1e-5])
+def test_gradient_magnitude_does_not_matter(env, sigma):
+    # Gradients of weak-column tuning are small: with dy ~ 1e-3 and step sizes of 1e-3..1e-2 the fp16 product
+    # dy * s would be a subnormal number.  The library scales dy by a power of two first; the error against the
+    # oracle must stay at the forward path's bar on top of what rounding the exact result to fp16 costs (at
+    # sigma = 1e-5 dx itself is a subnormal fp16 number).
+    L = make_layer(LayerSpec("small_dy", 512, 2048, 3, 128, 8, 612))
+    batch = 24
+    x = make_x(L, batch)
+    rng = np.random.default_rng(17)
+    dy = rng.normal(0, sigma, size=(batch, L.d_out)).astype(np.float16)
+    dx, dww = run_gpu(env, L, x, dy)
+    rdx, rdww = backward.owq_backward_ref(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, L.weak_w, x, dy)
+    for n in range(batch):
+        den = np.linalg.norm(rdx[n])
+        rel_gpu = np.linalg.norm(dx[n].astype(np.float64) - rdx[n]) / den
+        rel_ideal = np.linalg.norm(owq_ref.to_fp16(rdx[n]).astype(np.float64) - rdx[n]) / den
+        assert rel_gpu <= 1.05 * rel_ideal + REL_L2, (sigma, n, rel_gpu, rel_ideal)
+    check_dww(dww, rdww, f"sigma {sigma}")
+
+
 def test_integer_case_is_exact(env):
     # Step size 1, zero point 0, dy in {-1, 0, 1}: every product and sum is a small integer, so dx must be
     # exact, whatever the order of the additions.
@@ -195,6 +216,18 @@ def test_errors(env):
     with pytest.raises(B.OwqError) as e:
         B.owq_backward_workspace_bytes(0, 4)
     assert e.value.status == B.OWQ_ERR_HANDLE
+
+
+def test_full_size_512_tokens_whole_output(env):
+    # configs[2]'s fc1 (4096 -> 16384) at the 512 tokens the benchmark times, the whole of dx and dww
+    torch, B = env
+    L = make_layer(CONFIGS[2][0])
+    batch = 512
+    x, dy = make_x(L, batch), make_dy(L, batch)
+    dx, dww = run_gpu(env, L, x, dy)
+    rdx, rdww = backward.owq_backward_ref(L.codes, L.scale, L.zero, L.group_size, L.weak_idx, L.weak_w, x, dy)
+    check_dx(dx, rdx, "fc1 512 tokens")
+    check_dww(dww, rdww, "fc1 512 tokens")
 
 
 def test_full_size_sampled(env):
