@@ -148,3 +148,40 @@ def candidate_errors(w16_group: np.ndarray, keep: np.ndarray, bits: int,
     for idx, _, _, _, e in grid(w32, bits, n_lo, n_hi, shrink):
         out[idx] = e
     return out
+
+
+def search_group_plain(w16: np.ndarray, keep: np.ndarray, bits: int, n_lo: int, n_hi: int, shrink: float):
+    """The same search with every decision taken from the plain definition in binary64: the cut
+    fractions, the narrowed range and the step size before its one rounding to fp16 are exact
+    quotients, the zero point is rint(-lo_i / s) and a code rint(w / s) + z with a true division
+    (not a multiplication by a rounded reciprocal).  Shares no arithmetic with the functions above
+    except the fp16 rounding of s, which is what the layer stores.  A test counts how often the
+    binary32 reading above decides differently from this one.
+
+    Returns (s fp16, z fp16, codes uint8 (0 at weak columns), error fp64, choice int)."""
+    codes = np.zeros(w16.size, dtype=np.uint8)
+    w = np.asarray(w16, dtype=np.float16).astype(np.float64)[keep]
+    if w.size == 0:
+        return np.float16(1.0), np.float16(0.0), codes, 0.0, 0
+    lo, hi = float(w.min()), float(w.max())
+    if hi == lo:
+        lo, hi = min(lo, 0.0), max(hi, 0.0)
+        if hi == lo:
+            return np.float16(1.0), np.float16(0.0), codes, 0.0, 0
+    qmax = (1 << bits) - 1
+    rng = hi - lo
+    best = None
+    for i in range(n_lo):
+        a = 0.0 if n_lo == 1 else shrink * i / (n_lo - 1)
+        for j in range(n_hi):
+            b = 0.0 if n_hi == 1 else shrink * j / (n_hi - 1)
+            lo_i, hi_j = lo + a * rng, hi - b * rng
+            s = float(np.float16(max((hi_j - lo_i) / qmax, 2.0 ** -14)))
+            z = float(min(max(np.rint(-lo_i / s), -2048.0), 2048.0)) + 0.0
+            q = np.clip(np.rint(w / s) + z, 0.0, float(qmax))
+            e = float(np.sum((w - s * (q - z)) ** 2))
+            if best is None or e < best[4]:
+                best = (i * n_hi + j, s, z, q, e)
+    idx, s, z, q, e = best
+    codes[keep] = q.astype(np.uint8)
+    return np.float16(s), np.float16(z), codes, e, idx

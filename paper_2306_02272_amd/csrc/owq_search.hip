@@ -25,7 +25,7 @@ typedef float f4v __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;            // waves per workgroup, each with its own LDS area
 constexpr int kChunk = 1024;         // columns moved through LDS at a time
-constexpr int kMaskBytesMax = 48 * 1024;   // LDS left for the weak-column bit mask of a row
+constexpr int kMaskBytesMax = 47 * 1024;   // LDS left for the weak-column bit mask of a row: 64 KiB less the kernel's static 16.1 KiB
 
 struct SearchArgs {
   const _Float16 *w;

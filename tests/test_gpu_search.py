@@ -171,9 +171,18 @@ def test_full_size_sampled_rows(env):
     # sampled rows against the oracle.
     w, idx = make_weights(16384, 4096, 32, seed=2000)
     got = run_gpu(env, w, idx, 3, 128, 16, 16, 0.4)
-    check_units(w, idx, 3, 128, 16, 16, 0.4, got, rows=[0, 4097, 16383])
+    rows = sorted(set(np.random.default_rng(3).integers(0, 16384, size=64).tolist() + [0, 4097, 16383]))
+    check_units(w, idx, 3, 128, 16, 16, 0.4, got, rows=rows)
     assert not got[2][:, idx].any()
     assert got[2].max() <= 7
+
+
+def test_longest_row_the_kernel_takes(env):
+    # d_in at the documented limit (the weak-column bit mask of a row fills the kernel's share of LDS): the call
+    # must be accepted and match the oracle
+    w, idx = make_weights(1, 385024, 3, seed=31)
+    got = run_gpu(env, w, idx, 3, 0, 4, 4, 0.3)
+    check_units(w, idx, 3, 0, 4, 4, 0.3, got)
 
 
 def test_repeatable(env):

@@ -221,5 +221,5 @@ def test_search_rejects_bad_arguments(lib):
     assert call(desc(shrink=-0.1)) == B.OWQ_ERR_SHAPE
     assert call(desc(shrink=float("nan"))) == B.OWQ_ERR_SHAPE
     assert call(desc(d_out=2 ** 31 - 1, d_in=2 ** 30, k=0)) == B.OWQ_ERR_SHAPE
-    # a row whose weak-column bit mask would not fit the kernel's share of LDS (48 KiB = 393216 columns)
-    assert call(desc(d_out=1, d_in=393216 + 32, group_size=0, k=0)) == B.OWQ_ERR_UNSUPPORTED
+    # a row whose weak-column bit mask would not fit the kernel's share of LDS (47 KiB = 385024 columns)
+    assert call(desc(d_out=1, d_in=385024 + 32, group_size=0, k=0)) == B.OWQ_ERR_UNSUPPORTED

@@ -155,3 +155,39 @@ def test_groups_are_searched_independently():
     # ragged last group
     r = search.search_config(w[:, :300], [5, 299], 4, 128, 2, 2, 0.2)
     assert r[0].shape == (3, 3) and not r[2][:, [5, 299]].any()
+
+
+def test_binary32_reading_against_the_plain_definition():
+    """The oracle takes every integer decision (s as fp16, z, q) in binary32 with a multiplication by
+    the rounded reciprocal 1/s, the arithmetic the library documents; the plain definition divides in
+    exact arithmetic.  Count, on the synthetic weights the GPU tests use, how often the two readings
+    decide differently, and bound what a difference can cost: a differing code sits on a rounding tie
+    of w/s (the two candidates are then equally far from w up to one ulp), a differing grid point or
+    zero point changes the error of the group by a relative amount far below the ranking tolerance of
+    the GPU parity test (2e-4)."""
+    from synth import make_weights
+    groups = diff_choice = diff_sz = diff_codes = codes_total = 0
+    worst = 0.0
+    for bits, seed in ((3, 5), (4, 6)):
+        w, idx = make_weights(24, 1024, 8, seed=seed)
+        keep = np.ones(1024, dtype=bool)
+        keep[idx] = False
+        for r in range(w.shape[0]):
+            for g in range(8):
+                sl = slice(128 * g, 128 * g + 128)
+                s1, z1, q1, e1, c1 = search.search_group(w[r, sl], keep[sl], bits, 16, 16, 0.4)
+                s2, z2, q2, e2, c2 = search.search_group_plain(w[r, sl], keep[sl], bits, 16, 16, 0.4)
+                groups += 1
+                diff_choice += int(c1 != c2)
+                diff_sz += int(c1 == c2 and (s1 != s2 or z1 != z2))
+                if c1 == c2 and s1 == s2 and z1 == z2:
+                    diff_codes += int(np.count_nonzero(q1 != q2))
+                    codes_total += int(keep[sl].sum())
+                worst = max(worst, abs(e1 - e2) / max(e2, 1e-30))
+    print(f"groups {groups}: other grid point {diff_choice}, same point other (s, z) {diff_sz}, "
+          f"codes differing {diff_codes} of {codes_total}, worst relative error difference {worst:.2e}")
+    assert groups == 384
+    assert diff_sz == 0                      # the stored step size and zero point agree wherever the grid point does
+    assert diff_choice <= groups // 50       # at most 2 % of the groups rank two near-equal candidates the other way
+    assert diff_codes <= codes_total // 2000
+    assert worst <= 2e-5
