@@ -491,7 +491,6 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
       const int t = a.task_id[n];
       if ((u32)t < (u32)a.n_sets) mine = t;
     }
-    const int t_last = a.task_id != nullptr ? a.n_sets - 1 : -1;
     typedef const __attribute__((address_space(1))) u32x4 *gptr_t;   // pointers read from memory: global
     constexpr int KS = 8;                            // K-steps whose loads are in flight together
     for (int s0 = 0; 2 * s0 < kunits; s0 += KS) {
@@ -503,8 +502,16 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
         bv[j] = xsrc[u < kunits ? u : 0];
         if (u >= kunits) bv[j] = (u32x4){0u, 0u, 0u, 0u};
       }
-      for (int t = -1; t <= t_last; ++t) {           // one pass per set that some token of the tile uses
-        if (__ballot(mine == t) == 0ull) continue;
+      // one pass per set that some token of the tile uses, in ascending order of the set index (at most
+      // 33 passes however many sets the table holds): the least index still pending in the wave is next
+      int pending = mine;
+      for (;;) {
+        int cand = pending >= -1 ? pending : 0x7fffffff;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) cand = min(cand, __shfl_xor(cand, d));
+        const int t = __builtin_amdgcn_readfirstlane(cand);
+        if (t == 0x7fffffff) break;
+        if (pending == t) pending = -2;
         const gptr_t wbase = t < 0 ? (gptr_t)a.weak_w : (gptr_t)static_cast<const u32x4 *>(a.weak_sets[t]);
         const gptr_t wsrc = wbase + (size_t)row * kunits;
         const bool use = mine == t;

@@ -73,6 +73,31 @@ def test_tokens_of_different_tasks_share_the_dense_matrix(env, case):
 
 
 @pytest.mark.parametrize("layout", [0, 1])
+def test_large_table_sparsely_used(env, layout):
+    # A serving table of 4096 tasks of which a batch uses five: only the entries some token selects are read
+    # (the others are null pointers here), and the cost must not grow with the table.
+    torch, B = env
+    layer = make_layer(LayerSpec("table", 1024, 200, 3, 128, 16, 91))
+    used = [3, 777, 778, 2048, 4095]
+    sets = make_sets(layer, len(used), 6)
+    lin = B.OwqLinear(layer, layout=layout)
+    small, bufs = lin.add_weak_sets(sets)
+    table = torch.zeros(4096, dtype=torch.int64, device="cuda")
+    table[torch.tensor(used, device="cuda")] = small
+    batch = 50
+    rng = np.random.default_rng(10)
+    pick = rng.integers(0, len(used) + 1, size=batch)                        # len(used): the layer's own columns
+    task = np.array([used[p] if p < len(used) else -1 for p in pick], dtype=np.int32)
+    x = make_x(layer, batch)
+    y = lin.multi(torch.from_numpy(x).cuda(), table, torch.from_numpy(task).cuda())
+    torch.cuda.synchronize()
+    want = owq_ref.owq_linear_multi_ref(layer.codes, layer.scale, layer.zero, layer.group_size, layer.weak_idx,
+                                        sets + [layer.weak_w], [int(p) for p in pick], x)
+    check(y.cpu().numpy(), want, "table")
+    lin.close()
+
+
+@pytest.mark.parametrize("layout", [0, 1])
 def test_one_task_for_all_tokens_equals_the_plain_call_bit_for_bit(env, layout):
     torch, B = env
     layer = make_layer(LayerSpec("same", 1024, 128, 3, 0, 16, 78))
