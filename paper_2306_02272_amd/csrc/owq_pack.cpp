@@ -344,3 +344,93 @@ LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit) {
 }
 
 }  // namespace owq
+
+// ---------------------------------------------------------------------------
+// entry points that need no GPU (see include/owq.h)
+// ---------------------------------------------------------------------------
+using namespace owq;
+
+extern "C" {
+
+owq_status_t owq_geometry(const owq_layer_desc_t *desc, owq_layer_info_t *info) {
+  if (!desc || !info) return OWQ_ERR_NULL;
+  return compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, info);
+}
+
+owq_status_t owq_packed_bytes(const owq_layer_desc_t *desc, size_t *bytes) {
+  if (!desc || !bytes) return OWQ_ERR_NULL;
+  owq_layer_info_t g;
+  owq_status_t st = compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, &g);
+  if (st != OWQ_OK) return st;
+  *bytes = (size_t)g.total_bytes;
+  return OWQ_OK;
+}
+
+owq_status_t owq_pack_host(const owq_layer_desc_t *desc, void *host_buf, size_t bytes) {
+  if (!desc || !host_buf) return OWQ_ERR_NULL;
+  owq_status_t st = validate_desc(desc);
+  if (st != OWQ_OK) return st;
+  owq_layer_info_t g;
+  compute_geometry(desc->d_out, desc->d_in, desc->bits, desc->group_size, desc->k, desc->layout, &g);
+  if (bytes < g.total_bytes) return OWQ_ERR_BUFFER;
+  pack_blob(desc, g, static_cast<uint8_t *>(host_buf));
+  return OWQ_OK;
+}
+
+owq_status_t owq_unpack_codes(const void *host_packed, const owq_layer_info_t *info, uint8_t *codes) {
+  if (!host_packed || !info || !codes) return OWQ_ERR_NULL;
+  owq_layer_info_t g;
+  owq_status_t st = compute_geometry(info->d_out, info->d_in, info->bits, info->group_size, info->k, info->layout, &g);
+  if (st != OWQ_OK) return st;
+  const uint32_t *dwords = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(host_packed) + g.off_codes);
+  const uint32_t *wmeta = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(host_packed) + g.off_wmask);
+  for (int32_t row = 0; row < g.d_out; ++row) {
+    const int32_t rt = row / g.r, rloc = row % g.r;
+    for (int32_t jin = 0; jin < g.d_in; ++jin) {
+      int32_t j = jin;             // stored column
+      if (g.layout == OWQ_LAYOUT_COMPACT) {
+        const uint32_t meta = wmeta[jin >> 3], m = meta & 0xffu;
+        if ((m >> (jin & 7)) & 1u) {          // weak columns are not stored: code 0
+          codes[(int64_t)row * g.d_in + jin] = 0;
+          continue;
+        }
+        j = jin - (int32_t)((meta >> 8) + (uint32_t)__builtin_popcount(m & ((1u << (jin & 7)) - 1u)));
+      }
+      int32_t cin, lane;
+      int64_t tile;
+      if (g.layout == OWQ_LAYOUT_TILE) {
+        const int32_t c256 = j % 256, c128 = c256 % 128, c16 = c128 % 16;
+        cin = 64 * (c256 / 128) + 8 * (c128 / 16) + c16 % 8;
+        lane = (c16 / 8) * kTileRows + rloc;
+        tile = (int64_t)rt * g.nbp + j / 256;
+      } else {
+        const int32_t blk = j / kBlockCols;
+        cin = j % kBlockCols;
+        tile = (int64_t)rt * g.nslab + blk / g.cw;
+        lane = rloc * g.cw + blk % g.cw;
+      }
+      int v, bit;          // dword of the lane, bit inside its 16-bit half
+      uint32_t code = 0;
+      const int half = cin & 1;
+      if (g.bits == 3) {
+        const int u = cin / 32, t = (cin % 32) / 2;
+        for (int b = 0; b < 3; ++b) {
+          const int sb = 3 * t + b;
+          v = 3 * u + sb / 16;
+          bit = sb % 16 + 16 * half;
+          const int64_t unit = (tile * g.chunks + v / 4) * g.nact + lane;
+          code |= ((dwords[unit * 4 + (v & 3)] >> bit) & 1u) << b;
+        }
+      } else {
+        v = cin / 8;
+        bit = 4 * ((cin % 8) / 2) + 16 * half;
+        const int64_t unit = (tile * g.chunks + v / 4) * g.nact + lane;
+        code = (dwords[unit * 4 + (v & 3)] >> bit) & 15u;
+      }
+      codes[(int64_t)row * g.d_in + jin] = (uint8_t)code;
+    }
+  }
+  return OWQ_OK;
+}
+
+}  // extern "C"
