@@ -1,0 +1,94 @@
+"""GPU parity at the benchmark configurations' own shapes and batches, over the WHOLE output.
+
+Every case packs the full-size layer in the launch configuration the benchmark times and compares
+all of y with the fp64 oracle (relative L2 <= 1e-3, max-abs <= 1e-2 rms, whole output and per
+token).  The shapes: the tiny 1024 x 1024 4-bit layer, the LLaMA-13B-like set (q/k/v/o, gate/up,
+down; 4-bit, groups of 128) at 1, 4 and 16 tokens on both layouts that serve few tokens, the
+OPT-66B-like feed-forward pair at 64 tokens, and two shapes no launch model was fitted on (a hidden
+size that is not a power of two times anything in the list, a very wide feed-forward layer).
+"""
+import numpy as np
+import pytest
+
+from oracle import owq_ref
+from synth import CONFIGS, LayerSpec, make_layer, make_x
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 1e-3
+MAX_ABS = 1e-2
+GEMV, TILE = 0, 1
+
+
+@pytest.fixture(scope="module")
+def env():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2306_02272_amd import binding
+    binding.lib()
+    torch.cuda.set_device(0)
+    return torch, binding
+
+
+_layers = {}
+
+
+def layer_of(spec):
+    if spec.name not in _layers:
+        _layers.clear()                      # one full-size layer in memory at a time
+        _layers[spec.name] = make_layer(spec)
+    return _layers[spec.name]
+
+
+def whole_output_check(env, spec, batch, layout):
+    torch, B = env
+    print(f"full-size {spec.name} {spec.d_in}->{spec.d_out} batch={batch} layout={layout}", flush=True)
+    layer = layer_of(spec)
+    x = make_x(layer, batch)
+    lin = B.OwqLinear(layer, layout=layout)
+    y = lin(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    lin.close()
+    want = owq_ref.owq_linear_layer(layer, x)
+    assert got.shape == want.shape
+    rel, mx = owq_ref.parity_errors(got, want)
+    assert rel <= REL_L2 and mx <= MAX_ABS, (spec.name, batch, layout, rel, mx)
+    for n in range(batch):
+        rel, mx = owq_ref.parity_errors(got[n], want[n])
+        assert rel <= REL_L2 and mx <= MAX_ABS, (spec.name, batch, layout, n, rel, mx)
+
+
+def test_tiny_1024x1024(env):
+    for layout in (GEMV, TILE):
+        whole_output_check(env, CONFIGS[0][0], 1, layout)
+
+
+LLAMA = [(li, batch, layout) for li in (0, 1, 2) for batch, layout in ((1, GEMV), (1, TILE), (4, TILE), (16, TILE))]
+
+
+@pytest.mark.parametrize("li,batch,layout", LLAMA, ids=[f"{CONFIGS[3][li].name}_b{b}_l{l}" for li, b, l in LLAMA])
+def test_llama13b_set(env, li, batch, layout):
+    whole_output_check(env, CONFIGS[3][li], batch, layout)
+
+
+def test_llama13b_gemv_layout_batch4(env):
+    whole_output_check(env, CONFIGS[3][1], 4, GEMV)
+
+
+@pytest.mark.parametrize("li", [0, 1])
+def test_opt66b_ffn_batch64_whole_output(env, li):
+    whole_output_check(env, CONFIGS[4][li], 64, TILE)
+
+
+# shapes off the points the launch models were fitted on
+UNSEEN = [LayerSpec("unseen.7168x7168", 7168, 7168, 3, 128, 72, 9001),
+          LayerSpec("unseen.8192x28672", 8192, 28672, 4, 128, 82, 9002),
+          LayerSpec("unseen.28672x8192", 28672, 8192, 4, 0, 287, 9003)]
+
+
+@pytest.mark.parametrize("spec", UNSEEN, ids=[s.name for s in UNSEEN])
+@pytest.mark.parametrize("batch,layout", [(1, GEMV), (8, TILE), (40, TILE)])
+def test_unseen_shapes(env, spec, batch, layout):
+    whole_output_check(env, spec, batch, layout)
