@@ -42,6 +42,8 @@ WORKLOADS = {
     "target": (5, [0], "bandwidth-target layer 16384->4096, 3-bit per-channel, k=128", 0, 1),
     "llama13b": (3, [0, 1, 2], "configs[3]: LLaMA-13B-like q/k/v/o, gate/up, down, 4-bit group 128, k=1%", 0, 1),
     "tiny": (0, [0], "configs[0]: 1024->1024, 4-bit per-channel, k=8", 0, 1),
+    "unseen-7168": (6, [0], "a shape no launch model was fitted on: 7168->7168 (hidden size not a power of two), 3-bit group 128, k=72", 0, 1),
+    "unseen-wide-ffn": (6, [1, 2], "a shape no launch model was fitted on: very wide FFN pair 8192->28672 (4-bit group 128, k=82) + 28672->8192 (4-bit per-channel, k=287)", 0, 1),
     "opt66b-ffn": (4, [0, 1], "configs[4]: OPT-66B-like FFN pair, fc1 9216->36864 (k=64) + fc2 36864->9216 (k=256), 3-bit per-channel, tile layout (matrix cores)", 1, 64),
 }
 

@@ -155,7 +155,7 @@ def _seed(cfg: int, layer_id: int) -> int:
     return 1000 * cfg + layer_id
 
 
-# The five workload families: index = position in the benchmark's config list.
+# The workload families: 0-4 = position in the benchmark's config list; 5 and 6 are extra layers.
 CONFIGS = {
     0: [LayerSpec("tiny", 1024, 1024, 4, 0, 8, _seed(0, 0), outlier=1.0)],
     1: [LayerSpec("opt6.7b.attn", 4096, 4096, 3, 0, 32, _seed(1, 0))],
@@ -168,6 +168,10 @@ CONFIGS = {
         LayerSpec("opt66b.fc2", 36864, 9216, 3, 0, 256, _seed(4, 1))],
     # the layer the bandwidth target is stated on: 16384 -> 4096, per channel
     5: [LayerSpec("target.16384x4096", 16384, 4096, 3, 0, 128, _seed(5, 0))],
+    # shapes no launch model was fitted on: a hidden size that is not a power of two, and a very wide FFN pair
+    6: [LayerSpec("unseen.7168x7168", 7168, 7168, 3, 128, 72, 9001),
+        LayerSpec("unseen.8192x28672", 8192, 28672, 4, 128, 82, 9002),
+        LayerSpec("unseen.28672x8192", 28672, 8192, 4, 0, 287, 9003)],
 }
 
 

@@ -83,9 +83,7 @@ def test_opt66b_ffn_batch64_whole_output(env, li):
 
 
 # shapes off the points the launch models were fitted on
-UNSEEN = [LayerSpec("unseen.7168x7168", 7168, 7168, 3, 128, 72, 9001),
-          LayerSpec("unseen.8192x28672", 8192, 28672, 4, 128, 82, 9002),
-          LayerSpec("unseen.28672x8192", 28672, 8192, 4, 0, 287, 9003)]
+UNSEEN = CONFIGS[6]
 
 
 @pytest.mark.parametrize("spec", UNSEEN, ids=[s.name for s in UNSEEN])
