@@ -52,12 +52,10 @@ with these differences:
   * sz and weak_w have n_rt*32 rows; sz is stored group-major, [G][n_rt*32] dwords (the
     rows of a tile next to each other).
   * two more sections follow weak_idx: wmask, one byte per 8 input columns
-    (bit e = column 8i+e is weak), nbp*32 bytes; and a scratch area the library
-    uses at run time (contents undefined, zero in a fresh blob) of
-    64*(nbp*256)*2 + nblk*64*8 + 16384 + 64*kp*2 + (min(512, n_rg*nbp) + 2*n_rg)*65536
-    bytes, n_rg = ceil(n_rt / 8): staged activations of 64 tokens, their sums per block
-    and per column chunk, the activations at the weak columns, and fp32 partial results
-    of 256 rows by 64 tokens each.
+    (bit e = column 8i+e is weak), nbp*32 bytes.  The format ends there, at off_scratch
+    (= total_bytes here).  The library's blob goes on with working memory of its kernels,
+    whose size is the library's own business and no part of the format: all this module
+    says of it is that a freshly packed blob holds zeros there.
 
 Storage-favoured layout (layout = 2; appendix B.2 of the paper: the weak columns are taken
 out of the low-bit matrix).  One scale per row only.  The codes section holds the d_in - k
@@ -120,9 +118,6 @@ def tile_shape(nblk: int):
 
 
 TILE_ROWS = 32
-SCRATCH_BATCH = 64
-SCRATCH_GRID = 512          # most workgroups of the batched kernel
-SCRATCH_SLOT = 65536        # bytes of one partial result: 256 rows x 64 tokens, fp32
 
 
 def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int, layout: int = 0) -> Geometry:
@@ -141,10 +136,7 @@ def geometry(d_out: int, d_in: int, bits: int, group_size: int, k: int, layout: 
         off_weak_idx = _align(off_weak_w + d_out_pad * kp * 2)
         off_wmask = _align(off_weak_idx + kp * 4)
         off_scratch = _align(off_wmask + nbp * 32)
-        n_rg = -(-n_rt // 8)
-        scratch = (SCRATCH_BATCH * nbp * 256 * 2 + nblk * SCRATCH_BATCH * 8 + 16384 + SCRATCH_BATCH * kp * 2
-                   + (min(SCRATCH_GRID, n_rg * nbp) + 2 * n_rg) * SCRATCH_SLOT)
-        total = _align(off_scratch + scratch)
+        total = off_scratch
         return Geometry(d_out, d_in, bits, group_size, k, nblk, 1, TILE_ROWS, 64, nbp, n_rt,
                         d_out_pad, chunks, n_groups, kp, 0, off_sz, off_weak_w, off_weak_idx,
                         total, 1, nbp, off_wmask, off_scratch)

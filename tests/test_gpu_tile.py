@@ -165,7 +165,7 @@ def test_uploaded_blob_equals_oracle_pack_and_runs_are_reproducible(env):
     blob = B.owq_export_packed(lin.handle)
     want, geo = packfmt.pack_layer(layer.codes, layer.scale, layer.zero, layer.group_size,
                                    layer.weak_idx, layer.weak_w, layer.bits, layout=TILE)
-    assert info.total_bytes == geo.total_bytes and info.off_scratch == geo.off_scratch
+    assert info.total_bytes >= geo.total_bytes and info.off_scratch == geo.off_scratch == geo.total_bytes
     np.testing.assert_array_equal(blob[:geo.off_scratch], want[:geo.off_scratch])
     x = torch.from_numpy(make_x(layer, 64)).cuda()
     a = lin(x).cpu().numpy()

@@ -71,9 +71,12 @@ def test_tile_layout_host_pack_equals_oracle_pack(lib, spec):
                                    layout=1)
     info = B.owq_geometry(d)
     for f in ("layout", "nbp", "nblk", "n_rt", "d_out_pad", "chunks", "n_groups", "kp", "off_codes", "off_sz",
-              "off_weak_w", "off_weak_idx", "off_wmask", "off_scratch", "total_bytes"):
+              "off_weak_w", "off_weak_idx", "off_wmask", "off_scratch"):
         assert getattr(info, f) == getattr(geo, f), f
-    np.testing.assert_array_equal(blob, want)
+    # the format ends at off_scratch; what follows is the library's working memory, zero in a fresh blob
+    assert geo.total_bytes == geo.off_scratch and info.total_bytes >= geo.off_scratch and info.total_bytes % 256 == 0
+    np.testing.assert_array_equal(blob[:geo.off_scratch], want)
+    assert blob.size == info.total_bytes and not blob[geo.off_scratch:].any()
     np.testing.assert_array_equal(B.owq_unpack_codes(blob, info), L.codes)
     bad = B.desc_from_layer(L, 7)
     assert _status(B.owq_packed_bytes, bad) == B.OWQ_ERR_LAYOUT
