@@ -142,6 +142,18 @@ def bench_search(args) -> int:
         ev1.record(stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        # what the vector units issue of the search's own five instructions on registers only, same run
+        word = torch.zeros(1, dtype=torch.float32, device="cuda")
+        alu_wgs, alu_trips = 256 * 8, 4096
+        B.owq_probe_alu(word.data_ptr(), alu_wgs, alu_trips, raw)
+        stream.synchronize()
+        ea0, ea1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ea0.record(stream)
+        for _ in range(5):
+            B.owq_probe_alu(word.data_ptr(), alu_wgs, alu_trips, raw)
+        ea1.record(stream)
+        stream.synchronize()
+        bare_tips = alu_wgs * 256 * alu_trips * 160 * 5 / (ea0.elapsed_time(ea1) * 1e-3) / 1e12
     wall_s, event_s = t1 - t0, ev0.elapsed_time(ev1) * 1e-3
     assert torch.isfinite(err).all() and int(codes.max()) <= (1 << bits) - 1
     weights = d_out * (d_in - k)
@@ -159,7 +171,10 @@ def bench_search(args) -> int:
                      "frac": round(tflops / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": stored_traffic(args.workload),
                      "kernel": f"owq_search_kernel<{-(-n_lo * n_hi // 64)}, {0 if gs == 0 or gs > 1024 else -(-gs // 64)}>",
                      "avg_launch_us": round(avg_launch_s * 1e6, 1), "flops_per_launch": flops,
-                     "instructions_per_s": round(5 * weights * n_lo * n_hi / avg_launch_s / 1e12, 2)},
+                     "instructions_per_s": round(5 * weights * n_lo * n_hi / avg_launch_s / 1e12, 2),
+                     "achievable": {"kind": "register-only loop of the same five fp32 instructions (T lane-instructions/s), same run",
+                                    "instructions_per_s": round(bare_tips, 2),
+                                    "frac_of_it": round(5 * weights * n_lo * n_hi / avg_launch_s / 1e12 / bare_tips, 4)}},
     }
     if not args.no_cpu_baseline:
         from oracle import search

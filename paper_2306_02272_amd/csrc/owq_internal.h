@@ -113,6 +113,7 @@ int device_lds_limit(int32_t *bytes);
 // Read-only streaming kernels (defined in owq_probe.hip).  Return a hipError_t as int.
 int launch_read(const void *dev, size_t bytes, int32_t workgroups, void *stream);
 int launch_empty(void *stream);
+int launch_alu(void *dev_word, int32_t workgroups, int32_t trips, void *stream);
 
 }  // namespace owq
 
