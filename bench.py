@@ -363,6 +363,7 @@ def main() -> int:
     xs = [torch.from_numpy(x).cuda() for x in xs_host]
     ys = [torch.empty((batch, s.d_out), dtype=torch.float16, device="cuda") for s in specs]
 
+    probe_out = [torch.empty_like(y) for y in ys]
     stream = torch.cuda.Stream()                  # default priority
     raw = stream.cuda_stream
     # what a call reads of a packed layer: all of it but the tile layout's scratch area
@@ -384,6 +385,12 @@ def main() -> int:
         for t in range(first_step, first_step + n):
             for lin, nbytes in zip(sets[t % copies], read_bytes):
                 B.owq_probe_read(lin.buf.data_ptr(), nbytes, workgroups, raw)
+
+    def read_write_steps(first_step: int, n: int, workgroups: int):
+        """The same reads, and each launch ends on a store of the size of the layer's output."""
+        for t in range(first_step, first_step + n):
+            for lin, nbytes, y in zip(sets[t % copies], read_bytes, probe_out):
+                B.owq_probe_read_write(lin.buf.data_ptr(), nbytes, workgroups, y.data_ptr(), int(y.numel()) * 2 & ~15, raw)
 
     def empty_steps(first_step: int, n: int):
         for _ in range(n * len(specs)):
@@ -451,6 +458,8 @@ def main() -> int:
                 r = median_of(timed(lambda f, n: read_steps(f, n, wgs), 3))
                 if best is None or r[1] < best[1]:
                     best = (wgs, r[1])
+            rw = median_of(timed(lambda f, n: read_write_steps(f, n, best[0]), 3))
+            context["read_write_stream_us"] = round(rw[1] / (args.steps * len(specs)) * 1e6, 3)
             empty = median_of(timed(empty_steps, 3))
             context["read_only_stream"] = {"workgroups": best[0],
                                            "us_per_call": round(best[1] / (args.steps * len(specs)) * 1e6, 3),
@@ -495,7 +504,8 @@ def main() -> int:
             roofline["achievable"] = {"kind": "read-only 128-bit stream over the same packed copies", "gbs": ro["gbs"],
                                       "us_per_call": ro["us_per_call"], "workgroups": ro["workgroups"],
                                       "frac_of_it": round(achieved / ro["gbs"], 4),
-                                      "empty_launch_us": context["empty_launch_us"]}
+                                      "empty_launch_us": context["empty_launch_us"],
+                                      "with_output_store_us_per_call": context["read_write_stream_us"]}
     result = {
         # the headline metric; other workloads say their own code width and batch
         "metric": f"effective HBM GB/s (% of peak) + us/call, {specs[0].bits}-bit OWQ linear, batch {batch}",

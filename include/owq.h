@@ -210,6 +210,8 @@ owq_status_t owq_linear_static(owq_handle_t h, const void *x, void *y, int32_t b
  * section "Acceleration on Real Device" compares kernel times): owq_probe_read enqueues one
  * launch that reads `bytes` bytes (a multiple of 16) of DEVICE memory dev_buf (16-byte aligned)
  * once with 128-bit loads from `workgroups` workgroups of 256 threads and computes nothing;
+ * owq_probe_read_write does the same and then writes out_bytes bytes (a multiple of 16) of DEVICE
+ * memory out (16-byte aligned), each workgroup its share, as a layer call ends on the store of y;
  * owq_probe_empty enqueues a launch of 256 workgroups that does nothing; owq_probe_alu enqueues
  * one launch of `workgroups` workgroups of 256 threads in which every thread issues, `trips`
  * times, 32 runs of the five fp32 instructions that owq_search_config spends per weight and grid
@@ -219,6 +221,8 @@ owq_status_t owq_linear_static(owq_handle_t h, const void *x, void *y, int32_t b
  * (workgroups out of [1, 65536], trips out of [1, 2^20], 64 GiB or more), OWQ_ERR_HIP.
  */
 owq_status_t owq_probe_read(const void *dev_buf, size_t bytes, int32_t workgroups, void *stream);
+owq_status_t owq_probe_read_write(const void *dev_buf, size_t bytes, int32_t workgroups, void *out, size_t out_bytes,
+                                  void *stream);
 owq_status_t owq_probe_empty(void *stream);
 owq_status_t owq_probe_alu(void *dev_word, int32_t workgroups, int32_t trips, void *stream);
 

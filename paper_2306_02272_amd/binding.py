@@ -29,7 +29,7 @@ OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT = 0, 1, 2
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
            "owq_open_packed", "owq_linear", "owq_free_layer", "owq_layer_info", "owq_export_packed", "owq_set_launch",
            "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_search_config",
-           "owq_backward_workspace_bytes", "owq_linear_backward", "owq_probe_read", "owq_probe_empty", "owq_probe_alu", "owq_workspace_bytes", "owq_linear_ws", "owq_linear_static",
+           "owq_backward_workspace_bytes", "owq_linear_backward", "owq_probe_read", "owq_probe_read_write", "owq_probe_empty", "owq_probe_alu", "owq_workspace_bytes", "owq_linear_ws", "owq_linear_static",
            "owq_status_str"]
 
 
@@ -102,6 +102,7 @@ def lib():
         L.owq_linear_ws.argtypes = [P, P, P, I32, P, SZ, P]
         L.owq_linear_static.argtypes = [P, P, P, I32, P]
         L.owq_probe_read.argtypes = [P, SZ, I32, P]
+        L.owq_probe_read_write.argtypes = [P, SZ, I32, P, SZ, P]
         L.owq_probe_empty.argtypes = [P]
         L.owq_probe_alu.argtypes = [P, C.c_int32, C.c_int32, P]
         for n in EXPORTS:
@@ -209,6 +210,11 @@ def owq_linear_static(handle: int, x_ptr: int, y_ptr: int, batch: int, stream: i
 
 def owq_probe_read(dev_ptr: int, nbytes: int, workgroups: int, stream: int = 0) -> None:
     _check(lib().owq_probe_read(C.c_void_p(dev_ptr), nbytes, workgroups, C.c_void_p(stream)), "owq_probe_read")
+
+
+def owq_probe_read_write(dev_ptr: int, nbytes: int, workgroups: int, out_ptr: int, out_bytes: int, stream: int = 0) -> None:
+    _check(lib().owq_probe_read_write(C.c_void_p(dev_ptr), nbytes, workgroups, C.c_void_p(out_ptr), out_bytes,
+                                      C.c_void_p(stream)), "owq_probe_read_write")
 
 
 def owq_probe_empty(stream: int = 0) -> None:

@@ -168,7 +168,15 @@ owq_status_t owq_probe_read(const void *dev_buf, size_t bytes, int32_t workgroup
   if (!dev_buf) return OWQ_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(dev_buf) % 16 != 0 || bytes % 16 != 0) return OWQ_ERR_BUFFER;
   if (workgroups < 1 || workgroups > 65536 || bytes / 16 > 0xffffffffull) return OWQ_ERR_SHAPE;
-  return launch_read(dev_buf, bytes, workgroups, stream) == 0 ? OWQ_OK : OWQ_ERR_HIP;
+  return launch_read(dev_buf, bytes, workgroups, nullptr, 0, stream) == 0 ? OWQ_OK : OWQ_ERR_HIP;
+}
+
+owq_status_t owq_probe_read_write(const void *dev_buf, size_t bytes, int32_t workgroups, void *out, size_t out_bytes, void *stream) {
+  if (!dev_buf || !out) return OWQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(dev_buf) % 16 != 0 || bytes % 16 != 0) return OWQ_ERR_BUFFER;
+  if (reinterpret_cast<uintptr_t>(out) % 16 != 0 || out_bytes % 16 != 0 || out_bytes > 0xffffffffull) return OWQ_ERR_BUFFER;
+  if (workgroups < 1 || workgroups > 65536 || bytes / 16 > 0xffffffffull) return OWQ_ERR_SHAPE;
+  return launch_read(dev_buf, bytes, workgroups, out, out_bytes, stream) == 0 ? OWQ_OK : OWQ_ERR_HIP;
 }
 
 owq_status_t owq_probe_empty(void *stream) { return launch_empty(stream) == 0 ? OWQ_OK : OWQ_ERR_HIP; }

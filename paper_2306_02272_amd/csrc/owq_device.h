@@ -51,4 +51,16 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
+// Sum over CW = 16, 32 or 64 consecutive lanes (a tile row of CW blocks), in a fixed order.  The
+// total is valid in the last 16 lanes of each group of CW lanes.
+template <int CW>
+__device__ __forceinline__ float tile_row_sum(float v) {
+  v = row16_sum(v);
+  if (CW >= 32)   // lane 15 of rows 0 and 2 of the wave added to rows 1 and 3
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xa, 0xf, false));
+  if (CW >= 64)   // lane 31 added to rows 2 and 3
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xc, 0xf, false));
+  return v;
+}
+
 }  // namespace owq

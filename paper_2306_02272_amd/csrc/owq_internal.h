@@ -111,7 +111,7 @@ int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit);   // LDS
 int device_lds_limit(int32_t *bytes);
 
 // Read-only streaming kernels (defined in owq_probe.hip).  Return a hipError_t as int.
-int launch_read(const void *dev, size_t bytes, int32_t workgroups, void *stream);
+int launch_read(const void *dev, size_t bytes, int32_t workgroups, void *out, size_t out_bytes, void *stream);
 int launch_empty(void *stream);
 int launch_alu(void *dev_word, int32_t workgroups, int32_t trips, void *stream);
 

@@ -34,7 +34,12 @@ namespace owq {
 // per workgroup then.
 // COMPACT: the layer stores only the columns that are not weak (storage-favoured layout): the
 // staging moves their activations together and drops the weak ones into their own array.
-template <int BITS, int DEPTH, bool HAS_WEAK, int XN, bool COMPACT = false>
+// DIRECT = 16, 32 or 64: a tile row holds ALL blocks of a row (one slab of that many blocks) and
+// no weak chunk lies beyond one per block: a wave then owns whole rows, adds the partials of a
+// tile row across its lanes right after the tile and stores y itself; no partials in LDS, no
+// second barrier, no reduction phase.  0: rows are shared by waves (several slabs) and added up
+// through LDS after the main loop.
+template <int BITS, int DEPTH, bool HAS_WEAK, int XN, bool COMPACT = false, int DIRECT = 0>
 __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const GemvPacked packed) {
   const GemvArgs a = packed.unpack();
   constexpr int CH = BITS == 3 ? 3 : 4;
@@ -102,7 +107,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   u32 off_c = 0, off_s = 0, off_w = 0;       // byte offsets of the next tile to fetch
   u32 str_c = 0, str_s = 0, str_w = 0;       // their strides per tile
   int fetched = 0;                           // tiles fetched so far for this item
-  int pidx = 0, pstr = 0;                    // LDS index of the partial, stride per tile
+  int pidx = 0, pstr = 0;                    // LDS index of the partial (DIRECT: output row), stride per tile
 
   auto set_item = [&](int it_) {
     const int q = (int)(((u32)it_ * a.nslab_magic) >> 16), s = it_ - q * a.nslab;
@@ -121,8 +126,19 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     off_w = wk ? (u32)(row * a.kchunks + blk) * 16u : 0u;
     str_w = wk ? (u32)(a.rsplit * a.r * a.kchunks) * 16u : 0u;
     fetched = 0;
-    pidx = (q * a.r + rloc) * a.ppitch + blk;
-    pstr = a.rsplit * a.r * a.ppitch;
+    pidx = DIRECT ? row : (q * a.r + rloc) * a.ppitch + blk;
+    pstr = DIRECT ? a.rsplit * a.r : a.rsplit * a.r * a.ppitch;
+  };
+  // the lane of a tile row that stores its sum (DIRECT): the first of the last 16 lanes
+  const bool storer = DIRECT && bloc == DIRECT - 16;
+  auto finish_tile = [&](float p, bool real) {
+    if (DIRECT) {
+      const float s = tile_row_sum<DIRECT ? DIRECT : 16>(p);
+      if (storer && real && pidx < a.d_out) yn[pidx] = (_Float16)s;
+    } else if (active && real) {
+      part[pidx] = p;
+    }
+    pidx += pstr;
   };
   // Fetch the next tile into slot d.  Past the last tile every lane reads byte 0
   // of its section instead (one cache line per load), so that the number of loads
@@ -281,9 +297,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     for (; it0 + DEPTH < niter_r; it0 += DEPTH) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        const float p = tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc);
-        if (active) part[pidx] = p;
-        pidx += pstr;
+        finish_tile(tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc), true);
         issue(d);
       }
     }
@@ -291,9 +305,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     if (niter_r > 0) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        const float p = tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc);
-        if (active && it0 + d < niter) part[pidx] = p;
-        pidx += pstr;
+        finish_tile(tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc), it0 + d < niter);
       }
     }
     item += nwaves;
@@ -302,6 +314,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) issue(d);
   }
+  if (DIRECT) return;
   __syncthreads();
 
   // ---- (5) add the partials of each row; weak chunks beyond one per block -------
@@ -363,7 +376,14 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 typedef void (*kernel_fn)(const GemvPacked);
 
 template <int BITS, int DEPTH, bool WEAK, bool COMPACT>
-static kernel_fn pick3(int xn) {
+static kernel_fn pick3(int xn, int direct) {
+  if constexpr (!COMPACT && DEPTH <= 4) {         // the shapes a wave can own whole rows of: 2048, 4096, 8192 columns
+    if (xn == 4) {
+      if (direct == 16) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, false, 16>;
+      if (direct == 32) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, false, 32>;
+      if (direct == 64) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, false, 64>;
+    }
+  }
   if (xn == 4) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, COMPACT>;
   if (xn == 8) return owq_gemv_kernel<BITS, DEPTH, WEAK, 8, COMPACT>;
   return owq_gemv_kernel<BITS, DEPTH, WEAK, 0, COMPACT>;
@@ -372,19 +392,19 @@ static kernel_fn pick3(int xn) {
 // The storage-favoured layout always runs the variant with weak columns (k = 0 stores the same
 // bytes as the other layout and takes the same kernel as it).
 template <int BITS>
-static kernel_fn pick2(int depth, bool weak, int xn, bool compact) {
+static kernel_fn pick2(int depth, bool weak, int xn, bool compact, int direct) {
   if (compact) {
-    if (depth == 2) return pick3<BITS, 2, true, true>(xn);
-    if (depth == 4) return pick3<BITS, 4, true, true>(xn);
-    return pick3<BITS, 8, true, true>(xn);
+    if (depth == 2) return pick3<BITS, 2, true, true>(xn, 0);
+    if (depth == 4) return pick3<BITS, 4, true, true>(xn, 0);
+    return pick3<BITS, 8, true, true>(xn, 0);
   }
-  if (depth == 2) return weak ? pick3<BITS, 2, true, false>(xn) : pick3<BITS, 2, false, false>(xn);
-  if (depth == 4) return weak ? pick3<BITS, 4, true, false>(xn) : pick3<BITS, 4, false, false>(xn);
-  return weak ? pick3<BITS, 8, true, false>(xn) : pick3<BITS, 8, false, false>(xn);
+  if (depth == 2) return weak ? pick3<BITS, 2, true, false>(xn, direct) : pick3<BITS, 2, false, false>(xn, direct);
+  if (depth == 4) return weak ? pick3<BITS, 4, true, false>(xn, direct) : pick3<BITS, 4, false, false>(xn, direct);
+  return weak ? pick3<BITS, 8, true, false>(xn, 0) : pick3<BITS, 8, false, false>(xn, 0);
 }
 
-static kernel_fn pick(int bits, int depth, bool weak, int xn, bool compact = false) {
-  return bits == 3 ? pick2<3>(depth, weak, xn, compact) : pick2<4>(depth, weak, xn, compact);
+static kernel_fn pick(int bits, int depth, bool weak, int xn, bool compact = false, int direct = 0) {
+  return bits == 3 ? pick2<3>(depth, weak, xn, compact, direct) : pick2<4>(depth, weak, xn, compact, direct);
 }
 
 int prepare_kernels(int32_t lds) {
@@ -392,11 +412,12 @@ int prepare_kernels(int32_t lds) {
   for (int bits = 3; bits <= 4; ++bits)
     for (int depth = 2; depth <= 8; depth *= 2)
       for (int w = 0; w < 3; ++w)            // without weak columns, with, storage-favoured
-        for (int xn = 0; xn <= 8; xn += 4) {
-          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(bits, depth, w != 0, xn, w == 2)),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-          if (e != hipSuccess) return (int)e;
-        }
+        for (int xn = 0; xn <= 8; xn += 4)
+          for (int direct = 0; direct <= 64; direct = direct ? direct * 2 : 16) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(bits, depth, w != 0, xn, w == 2, direct)),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return (int)e;
+          }
   return (int)hipSuccess;
 }
 
@@ -442,7 +463,9 @@ int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLay
   const int xn = !aligned ? 0 : (xper <= 4 ? 4 : 8);
   const dim3 grid((unsigned)s.nwg, (unsigned)batch, 1), block((unsigned)nthr, 1, 1);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  kernel_fn fn = pick(g.bits, s.depth, g.kp > 0, xn, compact);
+  // a wave owns whole rows when one tile row spans the row and every weak chunk rides with a block
+  const int direct = (!compact && g.nslab == 1 && (g.cw == 16 || g.cw == 32 || g.cw == 64) && g.kp / 8 <= g.nblk) ? g.cw : 0;
+  kernel_fn fn = pick(g.bits, s.depth, g.kp > 0, xn, compact, direct);
   hipLaunchKernelGGL(fn, grid, block, s.lds_bytes, st, a);
   return (int)hipGetLastError();
 }

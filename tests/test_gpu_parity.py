@@ -65,6 +65,13 @@ SMALL = [
     ("b3_k0", 1536, 64, 3, 128, 0, 1),
     ("b3_many_weak", 256, 40, 3, 0, 100, 2),        # more weak chunks than blocks
     ("b4_batch16", 1024, 128, 4, 128, 10, 16),
+    # one slab of 16, 32 or 64 blocks: a wave owns whole rows and stores them itself
+    ("b4_own32", 4096, 77, 4, 128, 40, 2),
+    ("b3_own32_k0", 4096, 64, 3, 0, 0, 1),
+    ("b3_own64", 8192, 50, 3, 0, 64, 2),
+    ("b4_own64_g", 8192, 33, 4, 1024, 82, 3),
+    ("b3_own16_kmax", 2048, 41, 3, 0, 128, 2),      # as many weak chunks as blocks
+    ("b3_16_kover", 2048, 41, 3, 0, 136, 2),        # one more: rows go through the shared reduction again
 ]
 
 
@@ -102,7 +109,21 @@ def test_one_hot_probing_is_bit_exact(env, bits, group):
     np.testing.assert_array_equal(y.view(np.uint16), want.view(np.uint16))
 
 
-@pytest.mark.parametrize("bits,group,d_in", [(3, 0, 4096), (4, 128, 2048), (3, 128, 1024)])
+@pytest.mark.parametrize("bits,d_in", [(3, 2048), (4, 4096), (3, 8192)])
+def test_one_hot_probing_of_sampled_columns_when_a_wave_owns_rows(env, bits, d_in):
+    # the same read-back as above on the row-owning variants (one slab of 16, 32, 64 blocks), 192 sampled columns
+    d_out, k = 37, 24
+    layer = make_layer(LayerSpec("onehot_own", d_in, d_out, bits, 128, k, 23 + bits))
+    rng = np.random.default_rng(d_in)
+    cols = np.unique(np.concatenate([rng.integers(0, d_in, size=160), layer.weak_idx[:16], [0, d_in - 1]]))
+    x = np.zeros((cols.size, d_in), dtype=np.float16)
+    x[np.arange(cols.size), cols] = 1
+    y = run_gpu(env, layer, x)
+    want = owq_ref.to_fp16(owq_ref.owq_linear_layer(layer, x))
+    np.testing.assert_array_equal(y.view(np.uint16), want.view(np.uint16))
+
+
+@pytest.mark.parametrize("bits,group,d_in", [(3, 0, 4096), (4, 128, 2048), (3, 128, 1024), (4, 0, 8192), (3, 128, 8192)])
 def test_integer_inputs_are_bit_exact(env, bits, group, d_in):
     # s = 2^-m, integer z, x in {-1, 0, 1}: every partial sum is a small dyadic number,
     # fp32 accumulation is exact, so y must equal the rounded oracle result bit for bit.
