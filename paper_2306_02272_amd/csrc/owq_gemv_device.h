@@ -69,36 +69,36 @@ static_assert(sizeof(GemvPacked) == 128, "two lines of kernel arguments");
 // Six 16-bit windows per half expose every field at an offset <= 7:
 //   d0 (bits 0..15), bytes 1..2 (8..23), d1 (16..31), bytes 3..4 (24..39),
 //   d2 (32..47), d2 >> 6.
-__device__ __forceinline__ void mac_quad3(u32 d0, u32 d1, u32 d2, const u32 *xq, const Magic &M, float &a0, float &a1) {
+__device__ __forceinline__ void mac_quad3(u32 d0, u32 d1, u32 d2, const u32 *xq, const Magic &M, float *acc) {
   const u32 w1 = __builtin_amdgcn_perm(d1, d0, 0x06030401u);   // (d0.b1, d1.b0, d0.b3, d1.b2)
   const u32 w3 = __builtin_amdgcn_perm(d2, d1, 0x06030401u);
   const u32 w5 = d2 >> 6;
-  a0 = dot2(andor(d0, field(3, 0), M.m[0]), xq[0], a0);
-  a1 = dot2(andor(d0, field(3, 3), M.m[3]), xq[1], a1);
-  a0 = dot2(andor(d0, field(3, 6), M.m[6]), xq[2], a0);
-  a1 = dot2(andor(w1, field(3, 1), M.m[1]), xq[3], a1);
-  a0 = dot2(andor(w1, field(3, 4), M.m[4]), xq[4], a0);
-  a1 = dot2(andor(w1, field(3, 7), M.m[7]), xq[5], a1);
-  a0 = dot2(andor(d1, field(3, 2), M.m[2]), xq[6], a0);
-  a1 = dot2(andor(d1, field(3, 5), M.m[5]), xq[7], a1);
-  a0 = dot2(andor(w3, field(3, 0), M.m[0]), xq[8], a0);
-  a1 = dot2(andor(w3, field(3, 3), M.m[3]), xq[9], a1);
-  a0 = dot2(andor(w3, field(3, 6), M.m[6]), xq[10], a0);
-  a1 = dot2(andor(d2, field(3, 1), M.m[1]), xq[11], a1);
-  a0 = dot2(andor(d2, field(3, 4), M.m[4]), xq[12], a0);
-  a1 = dot2(andor(d2, field(3, 7), M.m[7]), xq[13], a1);
-  a0 = dot2(andor(w5, field(3, 4), M.m[4]), xq[14], a0);
-  a1 = dot2(andor(w5, field(3, 7), M.m[7]), xq[15], a1);
+  acc[0] = dot2(andor(d0, field(3, 0), M.m[0]), xq[0], acc[0]);
+  acc[1] = dot2(andor(d0, field(3, 3), M.m[3]), xq[1], acc[1]);
+  acc[2] = dot2(andor(d0, field(3, 6), M.m[6]), xq[2], acc[2]);
+  acc[3] = dot2(andor(w1, field(3, 1), M.m[1]), xq[3], acc[3]);
+  acc[0] = dot2(andor(w1, field(3, 4), M.m[4]), xq[4], acc[0]);
+  acc[1] = dot2(andor(w1, field(3, 7), M.m[7]), xq[5], acc[1]);
+  acc[2] = dot2(andor(d1, field(3, 2), M.m[2]), xq[6], acc[2]);
+  acc[3] = dot2(andor(d1, field(3, 5), M.m[5]), xq[7], acc[3]);
+  acc[0] = dot2(andor(w3, field(3, 0), M.m[0]), xq[8], acc[0]);
+  acc[1] = dot2(andor(w3, field(3, 3), M.m[3]), xq[9], acc[1]);
+  acc[2] = dot2(andor(w3, field(3, 6), M.m[6]), xq[10], acc[2]);
+  acc[3] = dot2(andor(d2, field(3, 1), M.m[1]), xq[11], acc[3]);
+  acc[0] = dot2(andor(d2, field(3, 4), M.m[4]), xq[12], acc[0]);
+  acc[1] = dot2(andor(d2, field(3, 7), M.m[7]), xq[13], acc[1]);
+  acc[2] = dot2(andor(w5, field(3, 4), M.m[4]), xq[14], acc[2]);
+  acc[3] = dot2(andor(w5, field(3, 7), M.m[7]), xq[15], acc[3]);
 }
 
 // ---- 4-bit: 8 codes in one dword -------------------------------------------
 // Even columns in the low half, odd ones in the high half, pair t at bits [4t, 4t+4).
-__device__ __forceinline__ void mac_dword4(u32 d, const u32 *xq, const Magic &M, float &a0, float &a1) {
+__device__ __forceinline__ void mac_dword4(u32 d, const u32 *xq, const Magic &M, float *acc) {
   const u32 w = d >> 6;
-  a0 = dot2(andor(d, field(4, 0), M.m[0]), xq[0], a0);
-  a1 = dot2(andor(d, field(4, 4), M.m[4]), xq[1], a1);
-  a0 = dot2(andor(w, field(4, 2), M.m[2]), xq[2], a0);
-  a1 = dot2(andor(w, field(4, 6), M.m[6]), xq[3], a1);
+  acc[0] = dot2(andor(d, field(4, 0), M.m[0]), xq[0], acc[0]);
+  acc[1] = dot2(andor(d, field(4, 4), M.m[4]), xq[1], acc[1]);
+  acc[2] = dot2(andor(w, field(4, 2), M.m[2]), xq[2], acc[2]);
+  acc[3] = dot2(andor(w, field(4, 6), M.m[6]), xq[3], acc[3]);
 }
 
 // Per block and lane: X = sum of the block's activations, Bc = sum_j 2^(10-o_j) x_j.
@@ -130,7 +130,7 @@ __device__ __forceinline__ void block_sums(const u32 *xr, float &X, float &Bc) {
 template <int BITS, bool HAS_WEAK>
 __device__ __forceinline__ float tile_partial(const u32x4 *cb, u32 szw, const u32x4 &wkv, const u32x4 &xwr,
                                               const u32 *xr, const Magic &M, float X, float Bc) {
-  float a0 = 0.f, a1 = 0.f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};       // four chains of dependent multiply-adds: a lone wave on a SIMD issues them back to back
   if (BITS == 3) {
     u32 w[12];
 #pragma unroll
@@ -138,7 +138,7 @@ __device__ __forceinline__ float tile_partial(const u32x4 *cb, u32 szw, const u3
       w[4 * c] = cb[c].x; w[4 * c + 1] = cb[c].y; w[4 * c + 2] = cb[c].z; w[4 * c + 3] = cb[c].w;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) mac_quad3(w[3 * u], w[3 * u + 1], w[3 * u + 2], &xr[16 * u], M, a0, a1);
+    for (int u = 0; u < 4; ++u) mac_quad3(w[3 * u], w[3 * u + 1], w[3 * u + 2], &xr[16 * u], M, acc);
   } else {
     u32 w[16];
 #pragma unroll
@@ -146,10 +146,10 @@ __device__ __forceinline__ float tile_partial(const u32x4 *cb, u32 szw, const u3
       w[4 * c] = cb[c].x; w[4 * c + 1] = cb[c].y; w[4 * c + 2] = cb[c].z; w[4 * c + 3] = cb[c].w;
     }
 #pragma unroll
-    for (int v = 0; v < 16; ++v) mac_dword4(w[v], &xr[4 * v], M, a0, a1);
+    for (int v = 0; v < 16; ++v) mac_dword4(w[v], &xr[4 * v], M, acc);
   }
   const float sc = half_lo(szw), zp = half_hi(szw);
-  float p = (a0 + a1) - Bc;
+  float p = ((acc[0] + acc[1]) + (acc[2] + acc[3])) - Bc;
   p = __builtin_fmaf(-zp, X, p);
   p *= sc;
   if (HAS_WEAK) {

@@ -52,6 +52,10 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   uint4 *xw_u = smem + 16 * a.xpitch;                           // activations of the weak columns
   _Float16 *xw = reinterpret_cast<_Float16 *>(xw_u);
   float *part = reinterpret_cast<float *>(xw_u + xw_units);     // [rows of the workgroup][ppitch]
+  // scales and weak weights of the workgroup's rows (contiguous in the layer, copied as they are)
+  uint4 *lsz_u = xw_u + xw_units + ((a.rtw * a.r * a.ppitch + 3) >> 2);
+  const u32 *lsz = reinterpret_cast<const u32 *>(lsz_u);
+  uint4 *lwk_u = lsz_u + (((a.rtw * a.r * a.n_groups + 3) >> 2) + 1);
 
   const int tid = threadIdx.x, nthr = a.nthr;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
@@ -96,6 +100,24 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     }
   }
   if (HAS_WEAK && !COMPACT) idx0 = a.weak_idx[tid < a.kp ? tid : 0];
+  // The scales and the weak weights of the workgroup's rows are two contiguous pieces of the
+  // layer: fetched here with 16-byte loads and handed round through LDS, so that the weight
+  // stream below is the only thing the steady state asks memory for (every load instruction in
+  // flight takes one of a compute unit's few request slots, whatever its size).
+  const int rows_wg = (rt_end - rt0) * a.r;
+  const u32 sz0 = (u32)(rt0 * a.r * a.n_groups) * 4u, sz_al = sz0 & ~15u;
+  const int sz_units = rows_wg > 0 ? (int)((sz0 - sz_al + (u32)(rows_wg * a.n_groups) * 4u + 15u) >> 4) : 0;
+  const int wk_units = HAS_WEAK ? rows_wg * a.kchunks : 0;
+  const u32 wk0 = (u32)(rt0 * a.r * a.kchunks) * 16u;
+  constexpr int SU = 2;                       // units per thread fetched ahead; more follow in a loop
+  u32x4 szv[SU], wkv[SU];
+#pragma unroll
+  for (int j = 0; j < SU; ++j) {
+    const int i = tid + j * nthr;
+    szv[j] = *reinterpret_cast<const u32x4 *>(sz_b + (sz_al + (u32)(i < sz_units ? i : 0) * 16u));
+    if (HAS_WEAK)
+      wkv[j] = *((const __attribute__((address_space(1))) u32x4 *)(wk_b + (wk0 + (u32)(i < wk_units ? i : 0) * 16u)));
+  }
 
   // ---- (2) per-item state and the tile pipeline ---------------------------------
   u32x4 buf[DEPTH][CH];
@@ -104,9 +126,9 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   int item = wave;
   int blk = 0, niter = 0, niter_r = 0;
   bool wk = false;
-  u32 off_c = 0, off_s = 0, off_w = 0;       // byte offsets of the next tile to fetch
+  u32 off_c = 0, off_s = 0, off_w = 0;       // next tile to fetch: byte offset of its codes, LDS indices of its scales and weak chunk
   u32 str_c = 0, str_s = 0, str_w = 0;       // their strides per tile
-  int fetched = 0;                           // tiles fetched so far for this item
+  int fetched = 0, sided = 0;                // tiles whose codes / whose scales have been fetched so far for this item
   int pidx = 0, pstr = 0;                    // LDS index of the partial (DIRECT: output row), stride per tile
 
   auto set_item = [&](int it_) {
@@ -121,11 +143,12 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     const int row = rt * a.r + rloc;
     off_c = (u32)(rt * a.nslab + s) * tile_bytes + (u32)al * 16u;
     str_c = (u32)(a.rsplit * a.nslab) * tile_bytes;
-    off_s = (u32)(row * a.n_groups + grp) * 4u;
-    str_s = (u32)(a.rsplit * a.r * a.n_groups) * 4u;
-    off_w = wk ? (u32)(row * a.kchunks + blk) * 16u : 0u;
-    str_w = wk ? (u32)(a.rsplit * a.r * a.kchunks) * 16u : 0u;
-    fetched = 0;
+    const int rowl = q * a.r + rloc;            // row within the workgroup
+    off_s = ((sz0 - sz_al) >> 2) + (u32)(rowl * a.n_groups + grp);
+    str_s = (u32)(a.rsplit * a.r * a.n_groups);
+    off_w = wk ? (u32)(rowl * a.kchunks + blk) : 0u;
+    str_w = wk ? (u32)(a.rsplit * a.r * a.kchunks) : 0u;
+    fetched = 0; sided = 0;
     pidx = DIRECT ? row : (q * a.r + rloc) * a.ppitch + blk;
     pstr = DIRECT ? a.rsplit * a.r : a.rsplit * a.r * a.ppitch;
   };
@@ -149,11 +172,19 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 #pragma unroll
     for (int c = 0; c < CH; ++c)
       buf[d][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes_b + (oc + (u32)c * cs)));
-    szb[d] = *reinterpret_cast<const u32 *>(sz_b + (live ? off_s : 0u));
-    if (HAS_WEAK)
-      wkb[d] = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4 *)(wk_b + (live ? off_w : 0u)));
-    off_c += str_c; off_s += str_s; off_w += str_w;
+    off_c += str_c;
     ++fetched;
+  };
+  // The scales and the weak chunk of the same tile, from LDS (after the barrier that follows their staging).
+  auto side = [&](int d) {
+    const bool live = sided < niter;          // uniform
+    szb[d] = lsz[live ? off_s : 0u];
+    if (HAS_WEAK) {
+      const uint4 t4 = lwk_u[live ? off_w : 0u];
+      wkb[d] = (u32x4){t4.x, t4.y, t4.z, t4.w};
+    }
+    off_s += str_s; off_w += str_w;
+    ++sided;
   };
 
   // Only the first two tiles go out ahead of the activations' arrival: more would
@@ -277,6 +308,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
   // ---- (4) main loop over the wave's (slab, row split) items ----------------------
   Magic M;
   M.init();
+  bool side_staged = false;
   for (;;) {
     u32 xr[64];
 #pragma unroll
@@ -291,6 +323,25 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     }
     float X, Bc;
     block_sums<BITS>(xr, X, Bc);
+    if (!side_staged) {                       // first item only; same for the whole workgroup
+#pragma unroll
+      for (int j = 0; j < SU; ++j) {
+        const int i = tid + j * nthr;
+        if (i < sz_units) lsz_u[i] = make_uint4(szv[j].x, szv[j].y, szv[j].z, szv[j].w);
+        if (HAS_WEAK && i < wk_units) lwk_u[i] = make_uint4(wkv[j].x, wkv[j].y, wkv[j].z, wkv[j].w);
+      }
+      for (int i = tid + SU * nthr; i < sz_units; i += nthr)          // many groups or rows only
+        lsz_u[i] = *reinterpret_cast<const uint4 *>(sz_b + (sz_al + (u32)i * 16u));
+      if (HAS_WEAK)
+        for (int i = tid + SU * nthr; i < wk_units; i += nthr) {
+          const u32x4 v = *((const __attribute__((address_space(1))) u32x4 *)(wk_b + (wk0 + (u32)i * 16u)));
+          lwk_u[i] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+      __syncthreads();
+      side_staged = true;
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) side(d);
 
     int it0 = 0;
     // steady state: every tile of the trip is real; fetch DEPTH tiles ahead
@@ -299,6 +350,7 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
       for (int d = 0; d < DEPTH; ++d) {
         finish_tile(tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc), true);
         issue(d);
+        side(d);
       }
     }
     // last trip: nothing more to fetch; tiles past the end are computed on filler and dropped
@@ -395,10 +447,12 @@ template <int BITS>
 static kernel_fn pick2(int depth, bool weak, int xn, bool compact, int direct) {
   if (compact) {
     if (depth == 2) return pick3<BITS, 2, true, true>(xn, 0);
+    if (depth == 3) return pick3<BITS, 3, true, true>(xn, 0);
     if (depth == 4) return pick3<BITS, 4, true, true>(xn, 0);
     return pick3<BITS, 8, true, true>(xn, 0);
   }
   if (depth == 2) return weak ? pick3<BITS, 2, true, false>(xn, direct) : pick3<BITS, 2, false, false>(xn, direct);
+  if (depth == 3) return weak ? pick3<BITS, 3, true, false>(xn, direct) : pick3<BITS, 3, false, false>(xn, direct);
   if (depth == 4) return weak ? pick3<BITS, 4, true, false>(xn, direct) : pick3<BITS, 4, false, false>(xn, direct);
   return weak ? pick3<BITS, 8, true, false>(xn, 0) : pick3<BITS, 8, false, false>(xn, 0);
 }
@@ -410,7 +464,7 @@ static kernel_fn pick(int bits, int depth, bool weak, int xn, bool compact = fal
 int prepare_kernels(int32_t lds) {
   if (lds <= 64 * 1024) return (int)hipSuccess;
   for (int bits = 3; bits <= 4; ++bits)
-    for (int depth = 2; depth <= 8; depth *= 2)
+    for (int depth : {2, 3, 4, 8})
       for (int w = 0; w < 3; ++w)            // without weak columns, with, storage-favoured
         for (int xn = 0; xn <= 8; xn += 4)
           for (int direct = 0; direct <= 64; direct = direct ? direct * 2 : 16) {

@@ -262,8 +262,12 @@ int32_t lds_bytes_for(const owq_layer_info_t &g, int32_t rtw, int32_t *xpitch) {
   if (xpitch) *xpitch = pitch;
   const int64_t xs = (int64_t)16 * pitch * 16;
   const int64_t xw = ((int64_t)g.kp * 2 + 15) / 16 * 16;
-  const int64_t part = (int64_t)rtw * g.r * g.nblk * 4;
-  const int64_t total = xs + xw + part;
+  const int64_t part = ((int64_t)rtw * g.r * g.nblk * 4 + 15) / 16 * 16;
+  // the scales and the weak weights of the workgroup's rows, copied as they lie in the layer (scales from
+  // the 16-byte unit their first byte falls in: one unit more)
+  const int64_t sz = (((int64_t)rtw * g.r * g.n_groups + 3) / 4 + 1) * 16;
+  const int64_t wk = (int64_t)rtw * g.r * (g.kp / 8) * 16;
+  const int64_t total = xs + xw + part + sz + wk;
   return total > 0x7fffffff ? 0x7fffffff : (int32_t)total;
 }
 
@@ -290,7 +294,7 @@ bool shape_is_valid(const owq_layer_info_t &g, const LaunchShape &s) {
   if (s.rtw < 1 || s.rsplit < 1 || s.waves < 1 || s.waves > 8) return false;
   if (s.rtw % s.rsplit != 0) return false;
   if (((int64_t)g.nslab * s.rsplit) % s.waves != 0) return false;
-  if (s.depth != 2 && s.depth != 4 && s.depth != 8) return false;
+  if (s.depth != 2 && s.depth != 3 && s.depth != 4 && s.depth != 8) return false;
   if (s.depth == 8 && s.waves > 4) return false;   // that variant is built for 256 threads at most
   return true;
 }
@@ -338,7 +342,20 @@ LaunchShape default_shape(const owq_layer_info_t &g, int32_t lds_limit) {
       }
     }
   }
+  // Tiles in flight per wave.  Every load instruction in flight holds one of a compute unit's request slots
+  // (measured: beyond about 48 of them further loads wait at issue and the waves with them), and a deeper
+  // pipeline only pays with enough tiles per wave to fill it; a wave with several (slab, split) items drains
+  // its pipeline at every item, which a depth above 3 made worse on the layers measured.
   best.depth = 2;
+  if (best.rtw >= 1) {
+    const int iters = best.rtw / best.rsplit;
+    const int items_per_wave = (int)(((int64_t)g.nslab * best.rsplit) / best.waves);
+    if (iters >= 5) {
+      for (int d = 3; d <= 4; ++d)
+        if (best.waves * d * g.chunks <= 48) best.depth = d;
+      if (items_per_wave > 1 && best.depth > 3) best.depth = 3;
+    }
+  }
   if (best.rtw >= 1 && !make_magics(g, &best)) best.rtw = 0;
   return best;
 }
