@@ -67,7 +67,11 @@ constexpr int kSmallLdsMax = 80 * 1024;   // two workgroups per compute unit
 template <int BITS>
 __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
   constexpr int CH = BITS == 3 ? 3 : 4;
-  constexpr int NB = 6;                   // code buffers per wave: five blocks in flight behind the one in use
+  // Code buffers per wave: one block in flight behind the one in use.  More were slower, step by step
+  // (6 buffers: 15.1 / 20.1 us per call on the LLaMA-13B-like layers at 4 / 16 tokens, 4: 14.1 / 19.1,
+  // 2: 13.5 / 18.5): with eight waves on a compute unit the loads of deeper pipelines wait for request
+  // slots, and the set-up's loads wait behind them.
+  constexpr int NB = 2;
   constexpr int WK = 2;                   // k-steps of weak columns whose weights a wave fetches ahead of its blocks
   extern __shared__ u32x4 lds[];
 
@@ -104,10 +108,10 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
     }
   };
   fetch_codes(Buf<0>{}, wb0);
-  fetch_codes(Buf<1>{}, wb0 + 1);
-  fetch_codes(Buf<2>{}, wb0 + 2);
-  fetch_codes(Buf<3>{}, wb0 + 3);
-  fetch_codes(Buf<4>{}, wb0 + 4);
+  if constexpr (NB > 2) fetch_codes(Buf<1 % NB>{}, wb0 + 1);
+  if constexpr (NB > 3) fetch_codes(Buf<2 % NB>{}, wb0 + 2);
+  if constexpr (NB > 4) fetch_codes(Buf<3 % NB>{}, wb0 + 3);
+  if constexpr (NB > 5) fetch_codes(Buf<4 % NB>{}, wb0 + 4);
   __builtin_amdgcn_sched_barrier(0);         // the weight stream goes out first
 
   const int g_lo = b0 >> a.lg_bpg;
@@ -324,16 +328,16 @@ __global__ __launch_bounds__(256, 2) void owq_tile_small(const SmallArgs a) {
   while (b + NB <= wb1) {
     step(Buf<0>{});
     step(Buf<1>{});
-    step(Buf<2>{});
-    step(Buf<3>{});
-    step(Buf<4>{});
-    step(Buf<5>{});
+    if constexpr (NB > 2) step(Buf<2 % NB>{});
+    if constexpr (NB > 3) step(Buf<3 % NB>{});
+    if constexpr (NB > 4) step(Buf<4 % NB>{});
+    if constexpr (NB > 5) step(Buf<5 % NB>{});
   }
   if (b < wb1) step(Buf<0>{});
-  if (b < wb1) step(Buf<1>{});
-  if (b < wb1) step(Buf<2>{});
-  if (b < wb1) step(Buf<3>{});
-  if (b < wb1) step(Buf<4>{});
+  if constexpr (NB > 2) { if (b < wb1) step(Buf<1 % NB>{}); }
+  if constexpr (NB > 3) { if (b < wb1) step(Buf<2 % NB>{}); }
+  if constexpr (NB > 4) { if (b < wb1) step(Buf<3 % NB>{}); }
+  if constexpr (NB > 5) { if (b < wb1) step(Buf<4 % NB>{}); }
   if (b > wb0) {                               // the last block's scaling
     if ((b - 1 - wb0) & 1) scale_in(acc1, gi_prev); else scale_in(acc0, gi_prev);
   }
