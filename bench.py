@@ -307,6 +307,8 @@ def main() -> int:
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run a few plain device copies of 256 MiB, for scaling rocprofv3's byte counters")
     ap.add_argument("--replays", type=int, default=7, help="timed replays of the K steps; the median one is reported")
+    ap.add_argument("--ramp-ms", type=float, default=100.0,
+                    help="untimed replays of the same steps before the timed ones, until the GPU has been busy this long")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the context figures (one packed copy, single launch, read-only stream, empty launch)")
     ap.add_argument("--launch", default="", help="rtw,rsplit,waves,depth override for every layer (tuning)")
@@ -398,26 +400,38 @@ def main() -> int:
 
     def timed(body, replays):
         """body(first_step, n) enqueues n steps.  Graph mode: the n steps are one graph, replayed `replays` times,
-        every replay bracketed by synchronisation; eager mode: enqueued from Python every time.  Returns the
-        (wall seconds, event seconds) pairs."""
+        every replay bracketed by synchronisation; eager mode: enqueued from Python every time.  Before the timed
+        replays the same steps run untimed until the GPU has been busy for --ramp-ms milliseconds (at least once:
+        that also uploads the graph): a run of a few steps is over before the chip has reached its clocks, and would
+        read up to 10 % slower than the same steps in a long run.  Returns the (wall seconds, event seconds) pairs."""
         graph = None
         if args.mode == "graph":
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
                 body(args.warmup, args.steps)
-            graph.replay()                        # untimed: uploads the graph
-            stream.synchronize()
-        out = []
-        for _ in range(replays):
-            ev0 = torch.cuda.Event(enable_timing=True)
-            ev1 = torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            ev0.record(stream)
+        def once():
             if graph is not None:
                 graph.replay()
             else:
                 body(args.warmup, args.steps)
+        r0 = time.perf_counter()
+        untimed = 0
+        while untimed == 0 or (time.perf_counter() - r0) * 1e3 < args.ramp_ms:
+            once()
+            stream.synchronize()
+            untimed += 1
+        ramp.setdefault("untimed_replays", untimed)      # of the layer's own steps: the first call of this function
+        # events made (and recorded once) ahead of the timed region: creating one costs microseconds of idle GPU
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(replays)]
+        for e0, e1 in events:
+            e0.record(stream)
+            e1.record(stream)
+        out = []
+        for ev0, ev1 in events:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev0.record(stream)
+            once()
             ev1.record(stream)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
@@ -429,6 +443,7 @@ def main() -> int:
         return pairs[order[len(order) // 2]]
 
     context = {}
+    ramp = {}
     with torch.cuda.stream(stream):
         if args.pmc_calib:
             pmc_calibration(torch, stream)
@@ -527,7 +542,9 @@ def main() -> int:
         "us_per_call": round(wall_s / launches * 1e6, 3),
         # every replay is the same K steps; the line reports the median one (ms_per_step x steps = its wall time)
         "replays": {"n": len(walls), "ms_per_step_min": round(walls[0] / args.steps * 1e3, 6),
-                    "ms_per_step_median": round(ms_per_step, 6), "ms_per_step_max": round(walls[-1] / args.steps * 1e3, 6)},
+                    "ms_per_step_median": round(ms_per_step, 6), "ms_per_step_max": round(walls[-1] / args.steps * 1e3, 6),
+                    # untimed replays of the same K steps in front of the timed ones (graph upload, clocks)
+                    "untimed_before": ramp.get("untimed_replays", 0), "ramp_ms": args.ramp_ms},
         "roofline": roofline,
     }
     for key in ("one_copy_cache_resident", "single_launch_us"):
