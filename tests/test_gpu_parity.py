@@ -187,7 +187,7 @@ def test_launch_shapes_do_not_change_the_result(env):
     want = owq_ref.owq_linear_layer(layer, x)
     lin = B.OwqLinear(layer)
     xd = torch.from_numpy(x).cuda()
-    for rtw, rsplit, waves, depth in [(1, 1, 1, 2), (1, 1, 2, 4), (8, 2, 4, 2), (16, 4, 8, 4), (64, 1, 2, 4), (5, 5, 2, 2), (16, 2, 4, 8), (7, 1, 1, 8)]:
+    for rtw, rsplit, waves, depth in [(1, 1, 1, 2), (1, 1, 2, 4), (8, 2, 4, 2), (16, 4, 8, 4), (64, 1, 2, 4), (5, 5, 2, 2), (16, 2, 4, 8), (7, 1, 1, 8), (9, 3, 2, 3)]:
         B.owq_set_launch(lin.handle, rtw, rsplit, waves, depth)
         info = lin.info()
         print("shape", rtw, rsplit, waves, depth, "->", info.workgroups, info.lds_bytes, flush=True)
@@ -196,6 +196,30 @@ def test_launch_shapes_do_not_change_the_result(env):
         check(y.cpu().numpy(), want, f"shape {rtw},{rsplit},{waves},{depth}")
     with pytest.raises(B.OwqError):
         B.owq_set_launch(lin.handle, 4, 3, 2, 4)       # 3 does not divide 4
+    lin.close()
+
+
+@pytest.mark.parametrize("d_in,bits,group,k", [(4096, 3, 128, 64), (2048, 4, 256, 21), (8192, 3, 0, 40), (16384, 4, 1024, 130)])
+def test_launch_shapes_of_the_row_owning_and_deep_variants(env, d_in, bits, group, k):
+    # One slab of 16, 32, 64 blocks (a wave owns its rows) and two slabs (rows shared), a ragged number of rows,
+    # 2 to 4 tiles in flight, and shapes with so many rows per workgroup and so few threads that the staging of
+    # the scales and weak weights through LDS takes its loop beyond the units fetched ahead.
+    torch, B = env
+    layer = make_layer(LayerSpec("own_shapes", d_in, 203, bits, group, k, 31 + bits))
+    x = make_x(layer, 2)
+    want = owq_ref.owq_linear_layer(layer, x)
+    lin = B.OwqLinear(layer)
+    xd = torch.from_numpy(x).cuda()
+    nslab = lin.info().nslab
+    for rtw, rsplit, waves, depth in [(4, 2, 2, 3), (8, 4, 4, 4), (3, 1, 1, 3), (6, 2, 2, 4), (16, 1, 1, 3), (32, 1, 1, 2), (12, 4, 4, 3)]:
+        if (nslab * rsplit) % waves:
+            continue
+        B.owq_set_launch(lin.handle, rtw, rsplit, waves, depth)
+        info = lin.info()
+        print("shape", rtw, rsplit, waves, depth, "->", info.workgroups, info.lds_bytes, flush=True)
+        y = lin(xd)
+        torch.cuda.synchronize()
+        check(y.cpu().numpy(), want, f"{d_in}: shape {rtw},{rsplit},{waves},{depth}")
     lin.close()
 
 
