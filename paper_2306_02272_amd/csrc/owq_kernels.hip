@@ -38,7 +38,9 @@ namespace owq {
 // no weak chunk lies beyond one per block: a wave then owns whole rows, adds the partials of a
 // tile row across its lanes right after the tile and stores y itself; no partials in LDS, no
 // second barrier, no reduction phase.  0: rows are shared by waves (several slabs) and added up
-// through LDS after the main loop.
+// through LDS after the main loop, one partial per (row, block).  128: rows of several slabs of 64
+// blocks: a wave adds its tile row across the lanes as above and leaves one sum per (row, slab) in
+// LDS; after the barrier only the slabs' sums are left to add.
 template <int BITS, int DEPTH, bool HAS_WEAK, int XN, bool COMPACT = false, int DIRECT = 0>
 __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const GemvPacked packed) {
   const GemvArgs a = packed.unpack();
@@ -149,13 +151,16 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     off_w = wk ? (u32)(rowl * a.kchunks + blk) : 0u;
     str_w = wk ? (u32)(a.rsplit * a.r * a.kchunks) : 0u;
     fetched = 0; sided = 0;
-    pidx = DIRECT ? row : (q * a.r + rloc) * a.ppitch + blk;
-    pstr = DIRECT ? a.rsplit * a.r : a.rsplit * a.r * a.ppitch;
+    pidx = DIRECT == 128 ? (q * a.r + rloc) * a.nslab + s : DIRECT ? row : (q * a.r + rloc) * a.ppitch + blk;
+    pstr = DIRECT == 128 ? a.rsplit * a.r * a.nslab : DIRECT ? a.rsplit * a.r : a.rsplit * a.r * a.ppitch;
   };
   // the lane of a tile row that stores its sum (DIRECT): the first of the last 16 lanes
-  const bool storer = DIRECT && bloc == DIRECT - 16;
+  const bool storer = DIRECT && bloc == (DIRECT == 128 ? 64 : DIRECT) - 16;
   auto finish_tile = [&](float p, bool real) {
-    if (DIRECT) {
+    if (DIRECT == 128) {
+      const float s = tile_row_sum<64>(p);
+      if (storer && real) part[pidx] = s;
+    } else if (DIRECT) {
       const float s = tile_row_sum<DIRECT ? DIRECT : 16>(p);
       if (storer && real && pidx < a.d_out) yn[pidx] = (_Float16)s;
     } else if (active && real) {
@@ -366,8 +371,18 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) issue(d);
   }
-  if (DIRECT) return;
+  if (DIRECT && DIRECT != 128) return;
   __syncthreads();
+  if (DIRECT == 128) {
+    // the sums of a row's slabs, in slab order
+    for (int rs = tid; rs < (rt_end - rt0) * a.r; rs += nthr) {
+      float sum = 0.f;
+      for (int s = 0; s < a.nslab; ++s) sum += part[rs * a.nslab + s];
+      const int row = rt0 * a.r + rs;
+      if (row < a.d_out) yn[row] = (_Float16)sum;
+    }
+    return;
+  }
 
   // ---- (5) add the partials of each row; weak chunks beyond one per block -------
   // A group of 16 lanes takes up to four rows at a time: their LDS reads go out together
@@ -435,6 +450,7 @@ static kernel_fn pick3(int xn, int direct) {
       if (direct == 32) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, false, 32>;
       if (direct == 64) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, false, 64>;
     }
+    if (xn == 8 && direct == 128) return owq_gemv_kernel<BITS, DEPTH, WEAK, 8, false, 128>;
   }
   if (xn == 4) return owq_gemv_kernel<BITS, DEPTH, WEAK, 4, COMPACT>;
   if (xn == 8) return owq_gemv_kernel<BITS, DEPTH, WEAK, 8, COMPACT>;
@@ -467,7 +483,7 @@ int prepare_kernels(int32_t lds) {
     for (int depth : {2, 3, 4, 8})
       for (int w = 0; w < 3; ++w)            // without weak columns, with, storage-favoured
         for (int xn = 0; xn <= 8; xn += 4)
-          for (int direct = 0; direct <= 64; direct = direct ? direct * 2 : 16) {
+          for (int direct = 0; direct <= 128; direct = direct ? direct * 2 : 16) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(bits, depth, w != 0, xn, w == 2, direct)),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
             if (e != hipSuccess) return (int)e;
@@ -518,7 +534,10 @@ int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLay
   const dim3 grid((unsigned)s.nwg, (unsigned)batch, 1), block((unsigned)nthr, 1, 1);
   hipStream_t st = static_cast<hipStream_t>(stream);
   // a wave owns whole rows when one tile row spans the row and every weak chunk rides with a block
-  const int direct = (!compact && g.nslab == 1 && (g.cw == 16 || g.cw == 32 || g.cw == 64) && g.kp / 8 <= g.nblk) ? g.cw : 0;
+  // (several slabs of 64 blocks: the waves still add their tile rows themselves, 128)
+  const int direct = (compact || g.kp / 8 > g.nblk) ? 0
+                     : (g.nslab == 1 && (g.cw == 16 || g.cw == 32 || g.cw == 64)) ? g.cw
+                     : (g.nslab > 1 && g.cw == 64) ? 128 : 0;
   kernel_fn fn = pick(g.bits, s.depth, g.kp > 0, xn, compact, direct);
   hipLaunchKernelGGL(fn, grid, block, s.lds_bytes, st, a);
   return (int)hipGetLastError();
