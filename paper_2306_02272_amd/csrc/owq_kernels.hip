@@ -180,6 +180,27 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
     off_c += str_c;
     ++fetched;
   };
+  // The same for the item after the current one: its first DEPTH tiles go out behind the current item's last
+  // ones, so that the pipeline does not drain where a wave changes slab.
+  u32 nf_off = 0, nf_str = 0;
+  int nf_n = 0, nf_done = 0;
+  auto peek_item = [&](int it_) {
+    const int q = (int)(((u32)it_ * a.nslab_magic) >> 16), s = it_ - q * a.nslab;
+    const int span = rt_end - rt0 - q;
+    nf_n = span > 0 ? (int)(((u32)(span + a.rsplit - 1) * a.rsplit_magic) >> 16) : 0;
+    nf_off = (u32)((rt0 + q) * a.nslab + s) * tile_bytes + (u32)al * 16u;
+    nf_str = (u32)(a.rsplit * a.nslab) * tile_bytes;
+    nf_done = 0;
+  };
+  auto issue_next = [&](int d) {
+    const bool live = nf_done < nf_n;         // uniform
+    const u32 oc = live ? nf_off : 0u, cs = live ? chunk_bytes : 0u;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+      buf[d][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes_b + (oc + (u32)c * cs)));
+    nf_off += nf_str;
+    ++nf_done;
+  };
   // The scales and the weak chunk of the same tile, from LDS (after the barrier that follows their staging).
   auto side = [&](int d) {
     const bool live = sided < niter;          // uniform
@@ -358,18 +379,33 @@ __global__ __launch_bounds__(DEPTH == 8 ? 256 : 512) void owq_gemv_kernel(const 
         side(d);
       }
     }
-    // last trip: nothing more to fetch; tiles past the end are computed on filler and dropped
-    if (niter_r > 0) {
+    // last trip of the item: tiles past its end are computed on filler and dropped; behind each tile goes a
+    // tile of the wave's next item, if it has one
+    const bool more = item + nwaves < a.items;
+    const bool ahead = more && niter_r > 0;
+    if (ahead) {
+      peek_item(item + nwaves);
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        finish_tile(tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc), it0 + d < niter);
+        issue_next(d);
+      }
+    } else if (niter_r > 0) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
         finish_tile(tile_partial<BITS, HAS_WEAK>(buf[d], szb[d], wkb[d], xwr, xr, M, X, Bc), it0 + d < niter);
       }
     }
+    if (!more) break;
     item += nwaves;
-    if (item >= a.items) break;
     set_item(item);
+    if (ahead) {
+      off_c = nf_off;                          // DEPTH tiles of this item are in flight already
+      fetched = DEPTH;
+    } else {
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) issue(d);
+      for (int d = 0; d < DEPTH; ++d) issue(d);
+    }
   }
   if (DIRECT && DIRECT != 128) return;
   __syncthreads();
