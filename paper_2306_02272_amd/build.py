@@ -11,7 +11,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["owq_api.cpp", "owq_pack.cpp", "owq_kernels.hip", "owq_tile.hip", "owq_tile_small.hip",
+SOURCES = ["owq_api.cpp", "owq_pack.cpp", "owq_kernels.hip", "owq_gemv_multi.hip", "owq_tile.hip", "owq_tile_small.hip",
            "owq_search.hip", "owq_backward.hip", "owq_probe.hip"]
 LIB = os.path.join(HERE, "libowq.so")
 NOISE = "is not a recognized feature for this target"

@@ -28,7 +28,7 @@ static owq_status_t make_handle(const owq_layer_info_t &g, void *dev_buf, owq_ha
   } else {
     shape = default_shape(g, lds_limit);
     if (shape.rtw < 1) return OWQ_ERR_UNSUPPORTED;
-    if (prepare_kernels(lds_limit) != 0) return OWQ_ERR_HIP;
+    if (prepare_kernels(lds_limit) != 0 || prepare_multi_kernels(lds_limit) != 0) return OWQ_ERR_HIP;
   }
   owq_layer_s *h = new (std::nothrow) owq_layer_s;
   if (!h) return OWQ_ERR_BUFFER;
@@ -104,7 +104,7 @@ static owq_status_t run_linear(owq_handle_t h, const TaskSets &tasks, const void
   const int herr = h->info.layout == OWQ_LAYOUT_TILE
                        ? launch_tile(h->info, h->dev_buf, sc ? sc->mem : nullptr, sc ? sc->bytes : 0, sc ? sc->grid : h->tile_grid,
                                      sc ? sc->split : h->tile_split, h->tile_waves, h->tile_small_split, tasks, x, y, batch, stream)
-                       : launch_gemv(h->info, h->shape, h->dev, tasks, x, y, batch, stream);
+                       : launch_gemv(h->info, h->shape, h->dev, tasks, x, y, batch, h->lds_limit, stream);
   if (herr == -2) return OWQ_ERR_SHAPE;     // a launch shape set by the caller does not fit this batch
   if (herr != 0) {
     h->info.last_hip_error = herr;

@@ -78,8 +78,13 @@ struct TaskSets {
   int32_t n_sets;
 };
 int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev, const TaskSets &tasks,
-                const void *x, void *y, int32_t batch, void *stream);
+                const void *x, void *y, int32_t batch, int32_t lds_limit, void *stream);
 int prepare_kernels(int32_t lds_bytes);   // raises the dynamic LDS limit when needed
+// Two tokens per pass over the weights (defined in owq_gemv_multi.hip): enqueues the first batch & ~1 tokens.
+// Returns a hipError_t as int, or -1 when the layer, the launch shape or x does not fit that kernel.
+int launch_gemv_multi(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev, int32_t lds_limit,
+                      const void *x, void *y, int32_t batch, void *stream);
+int prepare_multi_kernels(int32_t lds_bytes);
 
 // Tile path (defined in owq_tile.hip): three launches per pass of up to 64 tokens.
 // blob = DEVICE address of the packed blob; grid = workgroups of the main kernel.

@@ -539,7 +539,17 @@ int device_lds_limit(int32_t *bytes) {
 }
 
 int launch_gemv(const owq_layer_info_t &g, const LaunchShape &s, const DeviceLayer &dev, const TaskSets &tasks,
-                const void *x, void *y, int32_t batch, void *stream) {
+                const void *x, void *y, int32_t batch, int32_t lds_limit, void *stream) {
+  if (batch >= 2 && tasks.task_id == nullptr) {     // two tokens per pass over the weights, where that fits
+    const int r = launch_gemv_multi(g, s, dev, lds_limit, x, y, batch, stream);
+    if (r > 0) return r;
+    if (r == 0) {                                   // pairs done; an odd last token goes through the code below
+      if ((batch & 1) == 0) return 0;
+      x = static_cast<const _Float16 *>(x) + (size_t)(batch - 1) * g.d_in;
+      y = static_cast<_Float16 *>(y) + (size_t)(batch - 1) * g.d_out;
+      batch = 1;
+    }
+  }
   GemvPacked a;
   a.weak_sets = tasks.weak_sets; a.task_id = tasks.task_id; a.n_sets = tasks.n_sets;
   a.codes = static_cast<const u32x4 *>(dev.codes);
