@@ -309,6 +309,10 @@ def main() -> int:
     ap.add_argument("--replays", type=int, default=7, help="timed replays of the K steps; the median one is reported")
     ap.add_argument("--ramp-ms", type=float, default=100.0,
                     help="untimed replays of the same steps before the timed ones, until the GPU has been busy this long")
+    ap.add_argument("--lead-in", type=int, default=1, choices=(0, 1),
+                    help="1: every timed replay is enqueued straight behind an untimed one (GPU never idle at its start) and the "
+                         "line's value is the HIP-event time of its K steps; 0: every replay starts on an idle GPU and the value "
+                         "is the host clock around synchronize -> K steps -> synchronize")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the context figures (one packed copy, single launch, read-only stream, empty launch)")
     ap.add_argument("--launch", default="", help="rtw,rsplit,waves,depth override for every layer (tuning)")
@@ -398,12 +402,17 @@ def main() -> int:
         for _ in range(n * len(specs)):
             B.owq_probe_empty(raw)
 
-    def timed(body, replays):
+    def timed(body, replays, lead_in=None):
         """body(first_step, n) enqueues n steps.  Graph mode: the n steps are one graph, replayed `replays` times,
         every replay bracketed by synchronisation; eager mode: enqueued from Python every time.  Before the timed
         replays the same steps run untimed until the GPU has been busy for --ramp-ms milliseconds (at least once:
         that also uploads the graph): a run of a few steps is over before the chip has reached its clocks, and would
-        read up to 10 % slower than the same steps in a long run.  Returns the (wall seconds, event seconds) pairs."""
+        read up to 10 % slower than the same steps in a long run.  With a lead-in (--lead-in, the default) every timed
+        replay is enqueued straight behind an untimed replay of the same steps, with no synchronisation between the
+        two: the events then time exactly the K steps as they run in a job that keeps the GPU fed, without the
+        microseconds a first launch on an idle GPU takes to start (6 us of a 280 us region at 20 steps); the host
+        clock then brackets both replays.  Returns the (wall seconds, event seconds) pairs."""
+        lead_in = args.lead_in if lead_in is None else lead_in
         graph = None
         if args.mode == "graph":
             graph = torch.cuda.CUDAGraph()
@@ -430,6 +439,8 @@ def main() -> int:
         for ev0, ev1 in events:
             torch.cuda.synchronize()
             t0 = time.perf_counter()
+            if lead_in:
+                once()
             ev0.record(stream)
             once()
             ev1.record(stream)
@@ -438,8 +449,8 @@ def main() -> int:
             out.append((t1 - t0, ev0.elapsed_time(ev1) * 1e-3))
         return out
 
-    def median_of(pairs):
-        order = sorted(range(len(pairs)), key=lambda i: pairs[i][0])
+    def median_of(pairs, key=0):
+        order = sorted(range(len(pairs)), key=lambda i: pairs[i][key])
         return pairs[order[len(order) // 2]]
 
     context = {}
@@ -450,6 +461,7 @@ def main() -> int:
         run_steps(0, args.warmup)
         stream.synchronize()
         runs = timed(run_steps, args.replays)
+        idle = timed(run_steps, 3, lead_in=0) if args.lead_in else None
         if not args.no_context and tables is None:
             # (1) the same steps on ONE packed copy: the weights then come from the last-level cache
             one = median_of(timed(lambda f, n: run_steps(f, n, 1), 3))
@@ -480,10 +492,13 @@ def main() -> int:
                                            "us_per_call": round(best[1] / (args.steps * len(specs)) * 1e6, 3),
                                            "gbs": round(sum(read_bytes) * args.steps / best[1] / 1e9, 1)}
             context["empty_launch_us"] = round(empty[1] / (args.steps * len(specs)) * 1e6, 3)
-    wall_s, event_s = median_of(runs)
-    ms_per_step = wall_s / args.steps * 1e3
-    value = step_bytes / (wall_s / args.steps) / 1e9
-    walls = sorted(r[0] for r in runs)
+    # with a lead-in the K steps are timed by the events (the host clock brackets two replays); without, by the host clock
+    key = 1 if args.lead_in else 0
+    wall_s, event_s = median_of(runs, key)
+    step_s = (event_s if args.lead_in else wall_s) / args.steps
+    ms_per_step = step_s * 1e3
+    value = step_bytes / step_s / 1e9
+    walls = sorted(r[key] for r in runs)
 
     # parity of the last step against the oracle is checked in tests; here only a finite-ness guard
     for y in ys:
@@ -539,14 +554,21 @@ def main() -> int:
                    "packed_copies": copies, "launch_mode": args.mode, "tasks": args.tasks,
                    "bytes_per_step": step_bytes},
         "pct_of_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "us_per_call": round(wall_s / launches * 1e6, 3),
+        "us_per_call": round(step_s * args.steps / launches * 1e6, 3),
         # every replay is the same K steps; the line reports the median one (ms_per_step x steps = its wall time)
         "replays": {"n": len(walls), "ms_per_step_min": round(walls[0] / args.steps * 1e3, 6),
                     "ms_per_step_median": round(ms_per_step, 6), "ms_per_step_max": round(walls[-1] / args.steps * 1e3, 6),
                     # untimed replays of the same K steps in front of the timed ones (graph upload, clocks)
-                    "untimed_before": ramp.get("untimed_replays", 0), "ramp_ms": args.ramp_ms},
+                    "untimed_before": ramp.get("untimed_replays", 0), "ramp_ms": args.ramp_ms,
+                    "timed_by": ("HIP events around the K steps, enqueued straight behind an untimed replay of the same steps"
+                                 if args.lead_in else "host clock around synchronize, K steps, synchronize")},
         "roofline": roofline,
     }
+    if idle is not None:
+        # the same K steps started on an idle GPU, every replay between two synchronisations: host clock and events
+        iw, ie = median_of(idle)
+        result["replays"]["idle_start"] = {"n": len(idle), "ms_per_step_host_clock": round(iw / args.steps * 1e3, 6),
+                                           "ms_per_step_events": round(ie / args.steps * 1e3, 6)}
     for key in ("one_copy_cache_resident", "single_launch_us"):
         if key in context:
             result[key] = context[key]
