@@ -398,6 +398,17 @@ def main() -> int:
             for lin, nbytes, y in zip(sets[t % copies], read_bytes, probe_out):
                 B.owq_probe_read_write(lin.buf.data_ptr(), nbytes, workgroups, y.data_ptr(), int(y.numel()) * 2 & ~15, raw)
 
+    # the matrix instructions of one call's dense product, on registers only: 512 workgroups of four waves,
+    # 16 instructions of 32768 flops per trip (padding the batch to the 32 or 64 tokens the kernel multiplies)
+    probe_word = torch.zeros(4, dtype=torch.float32, device="cuda")
+    mfma_tokens = 32 if batch <= 32 else 64 * -(-batch // 64)
+    mfma_trips = [max(1, round(2 * mfma_tokens * sp.d_out * sp.d_in / (512 * 4 * 16 * 32768))) for sp in specs]
+
+    def mfma_steps(first_step: int, n: int):
+        for _ in range(n):
+            for trips in mfma_trips:
+                B.owq_probe_mfma(probe_word.data_ptr(), 512, trips, raw)
+
     def empty_steps(first_step: int, n: int):
         for _ in range(n * len(specs)):
             B.owq_probe_empty(raw)
@@ -492,6 +503,11 @@ def main() -> int:
                                            "us_per_call": round(best[1] / (args.steps * len(specs)) * 1e6, 3),
                                            "gbs": round(sum(read_bytes) * args.steps / best[1] / 1e9, 1)}
             context["empty_launch_us"] = round(empty[1] / (args.steps * len(specs)) * 1e6, 3)
+            if layout == 1 and batch > 16:
+                mf = median_of(timed(mfma_steps, 3))
+                mf_flops = sum(512 * 4 * 16 * 32768 * t for t in mfma_trips) * args.steps
+                context["mfma_only"] = {"us_per_call": round(mf[1] / (args.steps * len(specs)) * 1e6, 3),
+                                        "tflops": round(mf_flops / mf[1] / 1e12, 1)}
     # with a lead-in the K steps are timed by the events (the host clock brackets two replays); without, by the host clock
     key = 1 if args.lead_in else 0
     wall_s, event_s = median_of(runs, key)
@@ -521,6 +537,16 @@ def main() -> int:
                     "flops_per_launch": flops_per_step // len(specs),
                     "hbm_gbs": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBS, 4),
                     "workgroups": info.workgroups}
+        if "mfma_only" in context:
+            # the matrix instructions of the same calls issued from registers, nothing read or written: what the
+            # matrix cores deliver at the clock the chip holds under them; and the call's bytes at the read-only
+            # stream's rate
+            mo, ro = context["mfma_only"], context["read_only_stream"]
+            roofline["achievable"] = {"kind": "the same 32x32x16 fp16 matrix instructions on registers only, same stream and launch mode",
+                                      "tflops": mo["tflops"], "us_per_call": mo["us_per_call"],
+                                      "frac_of_it": round(tflops / mo["tflops"], 4),
+                                      "read_only_stream_us_per_call": ro["us_per_call"], "read_only_stream_gbs": ro["gbs"],
+                                      "empty_launch_us": context["empty_launch_us"]}
     else:
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,

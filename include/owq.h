@@ -217,7 +217,10 @@ owq_status_t owq_linear_static(owq_handle_t h, const void *x, void *y, int32_t b
  * times, 32 runs of the five fp32 instructions that owq_search_config spends per weight and grid
  * point (multiply, round, clamp, two fused multiply-adds) on registers only: 160 * trips
  * instructions per thread; dev_word = 4 bytes of DEVICE memory, 4-byte aligned, which it never
- * writes in practice.  Errors: OWQ_ERR_NULL, OWQ_ERR_BUFFER (alignment, size), OWQ_ERR_SHAPE
+ * writes in practice; owq_probe_mfma, with the same arguments and limits, has every wave issue
+ * `trips` times 16 of the 32x32x16 fp16 matrix instructions of the batched path into four
+ * independent accumulator tiles on registers only (two workgroups per compute unit as there):
+ * workgroups * 4 * trips * 16 * 32768 flops.  Errors: OWQ_ERR_NULL, OWQ_ERR_BUFFER (alignment, size), OWQ_ERR_SHAPE
  * (workgroups out of [1, 65536], trips out of [1, 2^20], 64 GiB or more), OWQ_ERR_HIP.
  */
 owq_status_t owq_probe_read(const void *dev_buf, size_t bytes, int32_t workgroups, void *stream);
@@ -225,6 +228,7 @@ owq_status_t owq_probe_read_write(const void *dev_buf, size_t bytes, int32_t wor
                                   void *stream);
 owq_status_t owq_probe_empty(void *stream);
 owq_status_t owq_probe_alu(void *dev_word, int32_t workgroups, int32_t trips, void *stream);
+owq_status_t owq_probe_mfma(void *dev_word, int32_t workgroups, int32_t trips, void *stream);
 
 /*
  * Weak-column tuning (section "Weak Column Tuning" of the paper: after quantisation only the

@@ -29,7 +29,7 @@ OWQ_LAYOUT_GEMV, OWQ_LAYOUT_TILE, OWQ_LAYOUT_COMPACT = 0, 1, 2
 EXPORTS = ["owq_geometry", "owq_packed_bytes", "owq_pack_host", "owq_unpack_codes", "owq_pack_layer",
            "owq_open_packed", "owq_linear", "owq_free_layer", "owq_layer_info", "owq_export_packed", "owq_set_launch",
            "owq_update_weak", "owq_weak_set_bytes", "owq_pack_weak_set", "owq_linear_multi", "owq_search_config",
-           "owq_backward_workspace_bytes", "owq_linear_backward", "owq_probe_read", "owq_probe_read_write", "owq_probe_empty", "owq_probe_alu", "owq_workspace_bytes", "owq_linear_ws", "owq_linear_static",
+           "owq_backward_workspace_bytes", "owq_linear_backward", "owq_probe_read", "owq_probe_read_write", "owq_probe_empty", "owq_probe_alu", "owq_probe_mfma", "owq_workspace_bytes", "owq_linear_ws", "owq_linear_static",
            "owq_status_str"]
 
 
@@ -105,6 +105,7 @@ def lib():
         L.owq_probe_read_write.argtypes = [P, SZ, I32, P, SZ, P]
         L.owq_probe_empty.argtypes = [P]
         L.owq_probe_alu.argtypes = [P, C.c_int32, C.c_int32, P]
+        L.owq_probe_mfma.argtypes = [P, C.c_int32, C.c_int32, P]
         for n in EXPORTS:
             getattr(L, n).restype = C.c_int
         L.owq_status_str.argtypes = [C.c_int]
@@ -219,6 +220,10 @@ def owq_probe_read_write(dev_ptr: int, nbytes: int, workgroups: int, out_ptr: in
 
 def owq_probe_empty(stream: int = 0) -> None:
     _check(lib().owq_probe_empty(C.c_void_p(stream)), "owq_probe_empty")
+
+
+def owq_probe_mfma(dev_word: int, workgroups: int, trips: int, stream: int = 0) -> None:
+    _check(lib().owq_probe_mfma(C.c_void_p(dev_word), workgroups, trips, C.c_void_p(stream)), "owq_probe_mfma")
 
 
 def owq_probe_alu(dev_word: int, workgroups: int, trips: int, stream: int = 0) -> None:

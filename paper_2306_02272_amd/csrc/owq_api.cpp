@@ -188,6 +188,13 @@ owq_status_t owq_probe_alu(void *dev_word, int32_t workgroups, int32_t trips, vo
   return launch_alu(dev_word, workgroups, trips, stream) == 0 ? OWQ_OK : OWQ_ERR_HIP;
 }
 
+owq_status_t owq_probe_mfma(void *dev_word, int32_t workgroups, int32_t trips, void *stream) {
+  if (!dev_word) return OWQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(dev_word) % 4 != 0) return OWQ_ERR_BUFFER;
+  if (workgroups < 1 || workgroups > 65536 || trips < 1 || trips > (1 << 20)) return OWQ_ERR_SHAPE;
+  return launch_mfma(dev_word, workgroups, trips, stream) == 0 ? OWQ_OK : OWQ_ERR_HIP;
+}
+
 owq_status_t owq_weak_set_bytes(owq_handle_t h, size_t *bytes) {
   if (!live(h)) return OWQ_ERR_HANDLE;
   if (!bytes) return OWQ_ERR_NULL;

@@ -119,6 +119,7 @@ int device_lds_limit(int32_t *bytes);
 int launch_read(const void *dev, size_t bytes, int32_t workgroups, void *out, size_t out_bytes, void *stream);
 int launch_empty(void *stream);
 int launch_alu(void *dev_word, int32_t workgroups, int32_t trips, void *stream);
+int launch_mfma(void *dev_word, int32_t workgroups, int32_t trips, void *stream);
 
 }  // namespace owq
 

@@ -5,6 +5,7 @@
 
 #include "owq_device.h"
 #include "owq_internal.h"
+#include "owq_tile_device.h"
 
 namespace owq {
 
@@ -72,6 +73,38 @@ __global__ __launch_bounds__(256) void owq_alu_kernel(float *out, int trips, flo
   if (e == -1.f) out[0] = e;          // never true (a sum of squares); keeps the loop alive
 }
 
+// The matrix instruction of the batched path on registers only: 16 of them per trip into four
+// independent accumulator tiles (what one k-step of owq_tile_mma issues for its 64 rows x 64
+// tokens, four times), two workgroups of four waves per compute unit as there.  What the matrix
+// cores deliver of this instruction at the clock the chip holds under it.
+__global__ __launch_bounds__(256, 2) void owq_mfma_kernel(float *out, int trips, float seed) {
+  const float lane = (float)(threadIdx.x & 63);
+  h8_t a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (_Float16)(seed * (1.f + 0.01f * lane + 0.1f * (float)i));
+    b[i] = (_Float16)(seed * (2.f - 0.01f * lane));
+  }
+  f16_t acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int t = 0; t < trips; ++t) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = mma(a, b, acc[i]);
+    asm volatile("" : "+v"(a), "+v"(b));   // keeps the trips apart for the compiler
+  }
+  float e = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) e += acc[i][r];
+  if (e == -1.f) out[0] = e;            // never true (sums of positive products); keeps the loop alive
+}
+
 __global__ void owq_empty_kernel(int never) {
   if (never == 0x7fffffff) g_probe_sink = 1;
 }
@@ -94,6 +127,13 @@ int launch_read(const void *dev, size_t bytes, int32_t workgroups, void *out, si
 int launch_alu(void *dev_word, int32_t workgroups, int32_t trips, void *stream) {
   hipLaunchKernelGGL(owq_alu_kernel, dim3((unsigned)workgroups, 1, 1), dim3(256, 1, 1), 0, static_cast<hipStream_t>(stream),
                      static_cast<float *>(dev_word), trips, 0.37f);
+  return (int)hipGetLastError();
+}
+
+// workgroups x 4 waves x trips x 16 matrix instructions of 2 * 32 * 32 * 16 flops
+int launch_mfma(void *dev_word, int32_t workgroups, int32_t trips, void *stream) {
+  hipLaunchKernelGGL(owq_mfma_kernel, dim3((unsigned)workgroups, 1, 1), dim3(256, 1, 1), 0, static_cast<hipStream_t>(stream),
+                     static_cast<float *>(dev_word), trips, 0.01f);
   return (int)hipGetLastError();
 }
 

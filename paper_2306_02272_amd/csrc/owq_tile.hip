@@ -231,10 +231,10 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
     cb[slot][rtl][c] = __builtin_nontemporal_load(src);
   };
   auto advance_codes = [&]() {
-    if (c_st + 1 < hi) {
-      ++c_st;
-      if (++c_bp == a.nbp) { c_bp = 0; ++c_rg; }
-    }
+    const bool more = c_st + 1 < hi, wrap = more && c_bp + 1 == a.nbp;
+    c_st += more ? 1 : 0;
+    c_rg += wrap ? 1 : 0;
+    c_bp = wrap ? 0 : c_bp + (more ? 1 : 0);
   };
   // Staging registers.  8 waves (4 or fewer units per thread): three sets rotating with the code
   // buffers, the tile of step st + 2 is fetched during step st and goes to LDS at the end of
@@ -270,10 +270,10 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
     }
   };
   auto advance_x = [&]() {
-    if (x_st + 1 < hi) {
-      ++x_st;
-      if (++x_bp == a.nbp) { x_bp = 0; ++x_rg; }
-    }
+    const bool more = x_st + 1 < hi, wrap = more && x_bp + 1 == a.nbp;
+    x_st += more ? 1 : 0;
+    x_rg += wrap ? 1 : 0;
+    x_bp = wrap ? 0 : x_bp + (more ? 1 : 0);
   };
   auto store_x = [&](int set, int buf) {
 #pragma unroll
@@ -424,7 +424,11 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
         clear(acc);
       }
     }
-    if (last_of_group) { bp = 0; ++rg; } else { ++bp; }
+    // as selects of values: an `if` that increments one of the two gets turned into one increment through a
+    // selected address, which puts both counters into scratch memory, and every wait for such a load is
+    // a wait for all the loads of codes in flight
+    rg += last_of_group ? 1 : 0;
+    bp = last_of_group ? 0 : bp + 1;
     store_x(XSETS == 3 ? (J + 1) % 3 : 0, par ^ 1);
     __syncthreads();
     par ^= 1;
