@@ -660,8 +660,12 @@ int32_t tile_grid_limit(const owq_layer_info_t &g, int32_t waves, uint64_t scrat
 // costs more than a tenth in steps per workgroup against equal ranges of the whole sequence.
 void tile_default_shape(const owq_layer_info_t &g, int32_t waves, int32_t *grid, int32_t *split, uint64_t scratch_bytes) {
   const int32_t limit = tile_grid_limit(g, waves, scratch_bytes);
-  int32_t cap = waves == 8 ? kTileGridMax / 2 : kTileGridMax;
-  if (g.n_groups > 1 && waves == 4) cap = kTileGridMax / 2;   // grouped layers: one workgroup per compute unit
+  // One workgroup per compute unit.  Two of four waves (which the registers allow for layers with one scale per
+  // row) are no faster per step, as the matrix cores and the memory stream take turns rather than overlap on
+  // this machine, and twice the workgroups write twice the partial results: 256 against 512 workgroups at 64
+  // tokens measured 30.2 / 36.1 us on a 16384 x 4096 layer, 50.0 / 56.5 us on 28672 x 8192, 62.3 / 64.0 us on
+  // 9216 x 36864.
+  int32_t cap = kTileGridMax / 2;
   if (cap > limit) cap = limit;
   const int64_t n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
   const int64_t steps = n_rg * g.nbp;
