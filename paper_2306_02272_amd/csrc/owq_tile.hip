@@ -469,6 +469,8 @@ struct FinishArgs {
 // token tile i & 1).
 __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
   __shared__ _Float16 out[64][72];     // [token][row], padded pitch
+  constexpr int kWeakPitch = 17;       // 16-byte units per staged row of a chunk of weak columns, odd
+  __shared__ u32x4 wstage[2][64 * kWeakPitch];   // weak weights of the 64 rows, gathered activations of the 64 tokens
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rg = blockIdx.x / a.waves, w = blockIdx.x - rg * a.waves;
   const int row_base = (rg * a.waves + w) * 64;
@@ -497,6 +499,40 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
     }
     typedef const __attribute__((address_space(1))) u32x4 *gptr_t;   // pointers read from memory: global
     constexpr int KS = 8;                            // K-steps whose loads are in flight together
+    if (a.task_id == nullptr) {
+      // One set, the layer's own.  A lane's operand is 16 bytes of its own row, so a wave reading operands
+      // straight from memory touches 64 cache lines per load, and the address path takes a cycle for each
+      // (4 of this kernel's 12 us).  Instead the workgroup copies the 64 rows x 16 units of a chunk of 8 K-steps
+      // with loads that cover whole lines (a quarter wave per row), weights and gathered activations alike,
+      // and the waves take their operands from LDS (odd pitch: no bank conflicts).
+      const int cu = tid & 15, cr = tid >> 4;
+      for (int s0 = 0; 2 * s0 < kunits; s0 += KS) {
+        const int u = 2 * s0 + cu, uc = u < kunits ? u : 0;
+        u32x4 ta[4], tb[4];
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          int r = row_base + cr + 16 * i4;
+          if (r > a.d_out_pad - 1) r = a.d_out_pad - 1;
+          ta[i4] = a.weak_w[(size_t)r * kunits + uc];
+          tb[i4] = a.xw[(size_t)(cr + 16 * i4) * kunits + uc];
+        }
+        if (s0 > 0) __syncthreads();                 // the operands of the last chunk have been read
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const u32x4 zero = {0u, 0u, 0u, 0u};
+          wstage[0][(cr + 16 * i4) * kWeakPitch + cu] = u < kunits ? ta[i4] : zero;
+          wstage[1][(cr + 16 * i4) * kWeakPitch + cu] = (u < kunits && cr + 16 * i4 < a.ntok) ? tb[i4] : zero;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+          if (2 * (s0 + j) >= kunits) continue;      // same for the whole workgroup
+          const u32x4 av = wstage[0][(rtl * 32 + (lane & 31)) * kWeakPitch + 2 * j + kg];
+          const u32x4 bw = wstage[1][n * kWeakPitch + 2 * j + kg];
+          wk = mma(__builtin_bit_cast(h8_t, av), __builtin_bit_cast(h8_t, bw), wk);
+        }
+      }
+    } else
     for (int s0 = 0; 2 * s0 < kunits; s0 += KS) {
       // the gathered activations of these K-steps are the same for every set: fetched once
       u32x4 bv[KS];
