@@ -273,7 +273,7 @@ owq_status_t owq_export_packed(owq_handle_t h, void *host_buf, size_t bytes);
  *   GEMV layout: row_tiles_per_wg >= 1; row_splits divides row_tiles_per_wg; waves_per_wg in
  *     [1, 8] divides nslab * row_splits; prefetch_depth in {2, 4, 8} (8 only with at most 4
  *     waves).
- *   Tile layout: waves_per_wg = 4 or 8.  row_splits = S > 0: every
+ *   Tile layout: waves_per_wg = 4 or 8 (layers with group-wise scales: 4 only).  row_splits = S > 0: every
  *     group of 64 * waves_per_wg rows is cut into S column ranges, one workgroup each
  *     (S <= d_in / 256; row_tiles_per_wg must be 0 or that number of workgroups).
  *     row_splits = 0 and row_tiles_per_wg = P > 0: the flattened (row group, 256-column step)

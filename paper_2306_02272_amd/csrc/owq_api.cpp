@@ -274,6 +274,7 @@ owq_status_t owq_set_launch(owq_handle_t h, int32_t rtw, int32_t rsplit, int32_t
     if (depth < -1 || depth >= 400 || (depth % 100 > 0 && !tile_small_split_ok(h->info, depth % 100))) return OWQ_ERR_SHAPE;
     const int32_t wv = waves ? waves : h->tile_waves;
     if (wv != 4 && wv != 8) return OWQ_ERR_SHAPE;
+    if (wv == 8 && h->info.n_groups > 1) return OWQ_ERR_SHAPE;      // grouped layers: four waves only
     const int32_t lim = tile_grid_limit(h->info, wv);
     if (lim < 1) return OWQ_ERR_UNSUPPORTED;
     int32_t gr = 0, sp = 0;

@@ -160,28 +160,31 @@ template <int S> __device__ std::integral_constant<int, S> kstep_index(KStep<S>)
 // between(KStep<S>) runs after the matrix instructions of k-step S have been issued: the
 // caller spreads its global loads over the k-steps there, so that the memory pipeline of
 // the compute unit works on them while the matrix cores run.
-template <int BITS, int NT, int S>
+// GROUPED: the first k-step of a 128-column block (k-steps 0 and 8) starts the four tiles from `zero`.
+template <int BITS, int NT, bool GROUPED, int S>
 struct KSteps {
   template <typename Between>
   static __device__ __forceinline__ void run(const u32 *wd0, const u32 *wd1, const u32x4 *xb, int lane,
-                                             const Magic &M, f16_t *acc, Between &between) {
+                                             const Magic &M, f16_t *acc, const f16_t &zero, Between &between) {
+    constexpr bool kFirst = GROUPED && (S & 7) == 0;
     const h8_t a0 = a_operand<BITS, S>(wd0, M), a1 = a_operand<BITS, S>(wd1, M);
     const h8_t b0 = __builtin_bit_cast(h8_t, xb[(S * 2 + 0) * 64 + lane]);
-    acc[0] = mma(a0, b0, acc[0]);
-    acc[2] = mma(a1, b0, acc[2]);
+    acc[0] = mma(a0, b0, kFirst ? zero : acc[0]);
+    acc[2] = mma(a1, b0, kFirst ? zero : acc[2]);
     if (NT == 2) {
       const h8_t b1 = __builtin_bit_cast(h8_t, xb[(S * 2 + 1) * 64 + lane]);
-      acc[1] = mma(a0, b1, acc[1]);
-      acc[3] = mma(a1, b1, acc[3]);
+      acc[1] = mma(a0, b1, kFirst ? zero : acc[1]);
+      acc[3] = mma(a1, b1, kFirst ? zero : acc[3]);
     }
     between(KStep<S>{});
-    KSteps<BITS, NT, S + 1>::run(wd0, wd1, xb, lane, M, acc, between);
+    KSteps<BITS, NT, GROUPED, S + 1>::run(wd0, wd1, xb, lane, M, acc, zero, between);
   }
 };
-template <int BITS, int NT>
-struct KSteps<BITS, NT, 16> {
+template <int BITS, int NT, bool GROUPED>
+struct KSteps<BITS, NT, GROUPED, 16> {
   template <typename Between>
-  static __device__ __forceinline__ void run(const u32 *, const u32 *, const u32x4 *, int, const Magic &, f16_t *, Between &) {}
+  static __device__ __forceinline__ void run(const u32 *, const u32 *, const u32x4 *, int, const Magic &, f16_t *, const f16_t &,
+                                             Between &) {}
 };
 
 template <int J> struct Slot {};   // tag: code buffer J of the three
@@ -198,9 +201,10 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
   constexpr int RTG = 2 * WAVES;                           // row tiles per row group
   constexpr int SLOT_UNITS = WAVES * 16 * 64;              // 16-byte units of one partial result
   constexpr int ROWS = WAVES * 64;
-  // LDS buffer of a step: the activation tile; for grouped layers also (scale, zero) as two
-  // floats per row and block of the step, and (sum x, sum c*x) per token and block
-  constexpr int SZ_UNITS = GROUPED ? ROWS : 0, BS_UNITS = GROUPED ? 64 : 0;
+  // LDS buffer of a step: the activation tile; for grouped layers also, per block of the step, the scales of
+  // the rows and their zero-points as floats (two planes of ROWS), and per block and token the two
+  // 16-byte units that hold sum c*x and sum x as the token operand of the correcting matrix instruction
+  constexpr int SZ_UNITS = GROUPED ? ROWS : 0, BS_UNITS = GROUPED ? 256 : 0;
   constexpr int BUF_UNITS = kUnitsPerTile + SZ_UNITS + BS_UNITS;
   static_assert(XU >= 1 && XU <= 8 && 8 + 2 * CH <= 16, "loads must fit the 16 k-steps");
   static_assert(THREADS >= ROWS / 2 + 64, "one thread per staged unit of scales and sums");
@@ -280,14 +284,34 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
     for (int j = 0; j < XU; ++j) lds[buf * BUF_UNITS + unit_of(j)] = xg[set][j];
     if constexpr (GROUPED) {
       if (tid < ROWS / 2) {
+        // four rows of block h: scales to plane 2h, zero-points to plane 2h + 1
+        const int h = tid / (ROWS / 4), r4 = tid - h * (ROWS / 4);
         const u32 d[4] = {auxg[set].x, auxg[set].y, auxg[set].z, auxg[set].w};
-        f4_t lo4 = {half_lo(d[0]), half_hi(d[0]), half_lo(d[1]), half_hi(d[1])};
-        f4_t hi4 = {half_lo(d[2]), half_hi(d[2]), half_lo(d[3]), half_hi(d[3])};
-        f4_t *dst = reinterpret_cast<f4_t *>(lds + buf * BUF_UNITS + kUnitsPerTile) + tid * 2;
-        dst[0] = lo4;
-        dst[1] = hi4;
+        float *pl = reinterpret_cast<float *>(lds + buf * BUF_UNITS + kUnitsPerTile) + 2 * h * ROWS + r4 * 4;
+        *reinterpret_cast<f4_t *>(pl) = (f4_t){half_lo(d[0]), half_lo(d[1]), half_lo(d[2]), half_lo(d[3])};
+        *reinterpret_cast<f4_t *>(pl + ROWS) = (f4_t){half_hi(d[0]), half_hi(d[1]), half_hi(d[2]), half_hi(d[3])};
       } else if (tid < ROWS / 2 + 64) {
-        lds[buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS + (tid - ROWS / 2)] = auxg[set];
+        // two tokens of one block: C = sum c*x and X = sum x in three bf16 pieces each (the top 16 bits of what
+        // is left, so the pieces add up to the float exactly), in the order the correcting instruction
+        // multiplies them: k = 0..7: C_h C_m C_l X_h X_m X_l X_h X_m; k = 8: X_l
+        const int u = tid - ROWS / 2;
+        u32x4 *dst = lds + buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS + ((u >> 5) * 64 + (u & 31) * 2) * 2;
+        auto pieces = [&](u32 xbits, u32 cbits, u32x4 *out) __attribute__((always_inline)) {
+          const float X = __builtin_bit_cast(float, xbits), Cs = __builtin_bit_cast(float, cbits);
+          const u32 ch = cbits & 0xffff0000u;
+          const float cr = Cs - __builtin_bit_cast(float, ch);
+          const u32 cm = __builtin_bit_cast(u32, cr) & 0xffff0000u;
+          const u32 cl = __builtin_bit_cast(u32, cr - __builtin_bit_cast(float, cm)) & 0xffff0000u;
+          const u32 xh = xbits & 0xffff0000u;
+          const float xr = X - __builtin_bit_cast(float, xh);
+          const u32 xmid = __builtin_bit_cast(u32, xr) & 0xffff0000u;
+          const u32 xl = __builtin_bit_cast(u32, xr - __builtin_bit_cast(float, xmid)) & 0xffff0000u;
+          out[0] = (u32x4){(ch >> 16) | cm, (cl >> 16) | xh, (xmid >> 16) | xl, (xh >> 16) | xmid};
+          out[1] = (u32x4){xl >> 16, 0u, 0u, 0u};
+        };
+        const u32x4 v = auxg[set];           // (sum x, sum c*x) of two tokens
+        pieces(v.x, v.y, dst);
+        pieces(v.z, v.w, dst + 2);
       }
     }
   };
@@ -340,6 +364,8 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
 
   Magic M;
   M.init();
+  // one scale per row: four tiles of raw sums over all columns.  Grouped: the four tiles are started from zero
+  // at every 128-column block, and `tot` holds the scaled sums.
   f16_t acc[4], tot[GROUPED ? 4 : 1];
   auto clear = [&](f16_t *v) {
 #pragma unroll
@@ -349,6 +375,9 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
   };
   clear(acc);
   if constexpr (GROUPED) clear(tot);
+  f16_t zero16;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) zero16[r] = 0.f;
   auto flush = [&](const f16_t *v, int slot) {
     f4_t *dst = a.slots + (size_t)slot * SLOT_UNITS + (w * 16) * 64 + lane;
 #pragma unroll
@@ -361,35 +390,48 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
       }
     }
   };
-  // grouped layers, after the 8 k-steps of block h of the step:
-  // tot += s * (acc - sum c*x - z * sum x) with the block's staged scales and sums; acc = 0
-  auto block_epilogue = [&](int h, int buf) __attribute__((always_inline)) {
-    const float *szl = reinterpret_cast<const float *>(lds + buf * BUF_UNITS + kUnitsPerTile);
-    const f2_t *bsl = reinterpret_cast<const f2_t *>(lds + buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS);
-    float X[2] = {0.f, 0.f}, Bc[2] = {0.f, 0.f};
+  // Grouped layers.  After the 8 k-steps of block h of a step one more matrix instruction per tile takes
+  // sum c*x + z * sum x away: A = (-1 -1 -1 -zh -zh -zh -zl -zl | -zl 0 ...) of the lane's row in bf16
+  // (zh + zl = z exactly, z being an fp16 number), B = the token's pieces staged with the step.  What is
+  // left is sum (q - z) x of the block, and `tot += s * acc` (scale_in) follows: one fused multiply-add per
+  // accumulator value.  (A second set of tiles, so that the scaling of one block could run under the matrix
+  // instructions of the next, does not fit the registers: 512 and 61 to 88 spilled.)
+  auto correct = [&](int h, int buf) __attribute__((always_inline)) {
+    const float *zpl = reinterpret_cast<const float *>(lds + buf * BUF_UNITS + kUnitsPerTile) + (2 * h + 1) * ROWS;
+    const u32x4 *bop = lds + buf * BUF_UNITS + kUnitsPerTile + SZ_UNITS + h * 128;
+    const int kg = lane >> 5;
+    u32x4 be[2];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const f2_t v = bsl[h * 64 + nt * 32 + (lane & 31)];
-      X[nt] = v.x;
-      Bc[nt] = v.y;
+    for (int nt = 0; nt < NT; ++nt) be[nt] = bop[(nt * 32 + (lane & 31)) * 2 + kg];
+#pragma unroll
+    for (int rtl = 0; rtl < 2; ++rtl) {
+      const float z = zpl[w * 64 + rtl * 32 + (lane & 31)];
+      const u32 zh = __builtin_bit_cast(u32, z) & 0xffff0000u;
+      const u32 zl = __builtin_bit_cast(u32, z - __builtin_bit_cast(float, zh)) & 0xffff0000u;
+      const u32 nzh = zh ^ 0x80000000u, nzl = zl ^ 0x80000000u;
+      const u32 m1 = 0xbf80u;                  // bf16 -1
+      const u32x4 ae = kg == 0 ? (u32x4){m1 | (m1 << 16), m1 | nzh, (nzh >> 16) | nzh, (nzl >> 16) | nzl}
+                               : (u32x4){nzl >> 16, 0u, 0u, 0u};
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        acc[rtl * 2 + nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf8_t, ae), __builtin_bit_cast(bf8_t, be[nt]), acc[rtl * 2 + nt], 0, 0, 0);
     }
+  };
+  auto scale_in = [&](int h, int buf) __attribute__((always_inline)) {
+    constexpr int kTot = GROUPED ? 1 : 0;
+    const float *spl = reinterpret_cast<const float *>(lds + buf * BUF_UNITS + kUnitsPerTile) + 2 * h * ROWS;
 #pragma unroll
     for (int rtl = 0; rtl < 2; ++rtl)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const f4_t *src = reinterpret_cast<const f4_t *>(szl + (size_t)(h * ROWS + w * 64 + rtl * 32 + 8 * q + 4 * (lane >> 5)) * 2);
-        const f4_t s01 = src[0], s23 = src[1];
-        const float sc[4] = {s01[0], s01[2], s23[0], s23[2]}, zp[4] = {s01[1], s01[3], s23[1], s23[3]};
+        const f4_t sc = *reinterpret_cast<const f4_t *>(spl + w * 64 + rtl * 32 + 8 * q + 4 * (lane >> 5));
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt) {
-            constexpr int kTot = GROUPED ? 1 : 0;
-            float v = acc[rtl * 2 + nt][4 * q + e] - Bc[nt];
-            v = __builtin_fmaf(-zp[e], X[nt], v);
-            tot[kTot * (rtl * 2 + nt)][4 * q + e] = __builtin_fmaf(sc[e], v, tot[kTot * (rtl * 2 + nt)][4 * q + e]);
-            acc[rtl * 2 + nt][4 * q + e] = 0.f;
-          }
+          for (int nt = 0; nt < NT; ++nt)
+            tot[kTot * (rtl * 2 + nt)][4 * q + e] =
+                __builtin_fmaf(sc[e], acc[rtl * 2 + nt][4 * q + e], tot[kTot * (rtl * 2 + nt)][4 * q + e]);
       }
   };
 
@@ -411,9 +453,12 @@ __global__ __launch_bounds__(WAVES * 64, GROUPED ? 1 : 2) void owq_tile_mma(cons
       if constexpr (S >= 8 && S < 8 + 2 * CH) fetch_code((J + 2) % 3, (S - 8) / CH, (S - 8) % CH);   // codes of step st + 2
       if constexpr (S == 8 + 2 * CH - 1) advance_codes();
       if constexpr (S == XU - 1) { fetch_aux(XF); advance_x(); }
-      if constexpr (GROUPED && (S == 7 || S == 15)) block_epilogue(S >> 3, par);
+      if constexpr (GROUPED && (S == 7 || S == 15)) {
+        correct(S >> 3, par);
+        scale_in(S >> 3, par);
+      }
     };
-    KSteps<BITS, NT, 0>::run(wd0, wd1, lds + par * BUF_UNITS, lane, M, acc, between);
+    KSteps<BITS, NT, GROUPED, 0>::run(wd0, wd1, lds + par * BUF_UNITS, lane, M, acc, zero16, between);
     const bool last_of_group = bp == a.nbp - 1;
     if (last_of_group || st == hi - 1) {
       if constexpr (GROUPED) {
@@ -647,8 +692,12 @@ typedef void (*mma_fn)(const TileArgs);
 
 template <int BITS, int WAVES>
 static mma_fn pick_mma2(int nt, bool grouped) {
-  if (nt == 2) return grouped ? owq_tile_mma<BITS, 2, true, WAVES> : owq_tile_mma<BITS, 2, false, WAVES>;
-  return grouped ? owq_tile_mma<BITS, 1, true, WAVES> : owq_tile_mma<BITS, 1, false, WAVES>;
+  if constexpr (WAVES == 4) {      // grouped layers: four waves only (their twelve accumulator tiles need a SIMD's registers)
+    if (grouped) return nt == 2 ? owq_tile_mma<BITS, 2, true, 4> : owq_tile_mma<BITS, 1, true, 4>;
+  } else {
+    if (grouped) return nullptr;
+  }
+  return nt == 2 ? owq_tile_mma<BITS, 2, false, WAVES> : owq_tile_mma<BITS, 1, false, WAVES>;
 }
 
 static mma_fn pick_mma(int bits, int nt, bool grouped, int waves) {
@@ -657,14 +706,14 @@ static mma_fn pick_mma(int bits, int nt, bool grouped, int waves) {
 }
 
 static int32_t tile_lds_bytes(bool grouped, int waves) {
-  return 2 * (kUnitsPerTile + (grouped ? waves * 64 + 64 : 0)) * 16;
+  return 2 * (kUnitsPerTile + (grouped ? waves * 64 + 256 : 0)) * 16;
 }
 
 // Grouped layers stage scales and sums next to the activations: more than the 64 KiB of LDS a
 // kernel may use without asking.  Returns a hipError_t as int.
 int prepare_tile_kernels(const owq_layer_info_t &g, int32_t lds_limit) {
   if (g.n_groups <= 1) return (int)hipSuccess;
-  for (int waves = 4; waves <= 8; waves += 4) {
+  for (int waves = 4; waves <= 4; waves += 4) {
     const int32_t need = tile_lds_bytes(true, waves);
     if (need > lds_limit) return (int)hipErrorInvalidValue;
     for (int nt = 1; nt <= 2; ++nt) {
@@ -729,6 +778,7 @@ int launch_tile(const owq_layer_info_t &g, void *blob, void *scratch, uint64_t s
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool grouped = g.n_groups > 1;
   if (waves != 4 && waves != 8) return (int)hipErrorInvalidValue;
+  if (grouped && waves != 4) return (int)hipErrorInvalidValue;
   if (grid < 1 || grid > tile_grid_limit(g, waves, scr_bytes)) return (int)hipErrorInvalidValue;
   const int n_rg = (g.n_rt + 2 * waves - 1) / (2 * waves);
   if (split < 0 || split > g.nbp || (split > 0 && grid != n_rg * split)) return (int)hipErrorInvalidValue;

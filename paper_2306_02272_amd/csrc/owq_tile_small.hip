@@ -34,7 +34,6 @@
 namespace owq {
 
 typedef u32 u32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf8_t __attribute__((ext_vector_type(8)));
 
 struct SmallArgs {
   const u32x4 *codes;
