@@ -116,6 +116,21 @@ def test_column_ranges_aligned_to_row_groups(env, split, waves):
     lin.close()
 
 
+def test_grouped_layers_take_four_waves_only(env):
+    torch, B = env
+    layer = make_layer(LayerSpec("g8", 1024, 300, 4, 128, 16, 33))
+    lin = B.OwqLinear(layer, layout=TILE)
+    with pytest.raises(B.OwqError) as e:
+        B.owq_set_launch(lin.handle, 0, 0, 8, 0)
+    assert e.value.status == B.OWQ_ERR_SHAPE
+    B.owq_set_launch(lin.handle, 0, 2, 4, 0)
+    x = make_x(layer, 64)
+    y = lin(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    check(y.cpu().numpy(), owq_ref.owq_linear_layer(layer, x), "grouped, two ranges")
+    lin.close()
+
+
 def test_all_columns_weak_reproduces_fp16_matmul(env):
     rng = np.random.default_rng(3)
     d_out, d_in = 48, 384
