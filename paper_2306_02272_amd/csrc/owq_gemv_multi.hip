@@ -392,12 +392,11 @@ int prepare_multi_kernels(int32_t lds) {
   for (int bits = 3; bits <= 4; ++bits)
     for (int depth = 2; depth <= 4; ++depth)
       for (int w = 0; w < 2; ++w)
-        for (int xn = 4; xn <= 8; xn += 4)
-          for (int ntok = 2; ntok <= 2; ntok += 2) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_multi(bits, depth, w != 0, xn, ntok)),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            if (e != hipSuccess) return (int)e;
-          }
+        for (int xn = 4; xn <= 8; xn += 4) {
+          const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_multi(bits, depth, w != 0, xn, 2)),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+          if (e != hipSuccess) return (int)e;
+        }
   return (int)hipSuccess;
 }
 
