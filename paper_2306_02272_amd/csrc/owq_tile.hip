@@ -509,9 +509,10 @@ struct FinishArgs {
   int scaled;            // the partial results are already scaled (grouped layers)
 };
 
-// grid = row groups x waves of the main kernel: one workgroup per 64 rows (the part of a slot
+// grid.x = row groups x waves of the main kernel: one workgroup per 64 rows (the part of a slot
 // one wave of the main kernel wrote); wave i takes accumulator tile i = (row tile i >> 1,
-// token tile i & 1).
+// token tile i & 1).  grid.y = 2 (layers with few rows, more than 32 tokens): a workgroup per token
+// tile as well, its waves sharing the row tiles as they do for 32 tokens or fewer.
 __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
   __shared__ _Float16 out[64][72];     // [token][row], padded pitch
   constexpr int kWeakPitch = 17;       // 16-byte units per staged row of a chunk of weak columns, odd
@@ -522,8 +523,9 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
   const size_t slot_units = (size_t)a.waves * 1024;
   // 64 tokens: wave = accumulator tile (row tile wv >> 1, token tile wv & 1), all four groups
   // of 8 rows; 32 tokens or fewer: two waves share a row tile, two groups of 8 rows each
-  const bool two = a.ntok > 32;
-  const int i = two ? wv : (wv >> 1) * 2, nt = i & 1, rtl = i >> 1;
+  const bool per_tile = gridDim.y == 2;
+  const bool two = a.ntok > 32 && !per_tile;
+  const int i = two ? wv : (wv >> 1) * 2 + (per_tile ? (int)blockIdx.y : 0), nt = i & 1, rtl = i >> 1;
   const int q0 = two ? 0 : 2 * (wv & 1), qn = two ? 4 : 2;
   const int n = nt * 32 + (lane & 31);
   // product of the fp16 weak columns with the activations gathered at their indices
@@ -679,8 +681,9 @@ __global__ __launch_bounds__(256) void owq_tile_finish(const FinishArgs a) {
     }
   }
   __syncthreads();
-  for (int e = tid; e < a.ntok * 64; e += 256) {
-    const int nn = e >> 6, r = e & 63;
+  const int n_lo = per_tile ? 32 * (int)blockIdx.y : 0, n_hi = per_tile ? min(a.ntok, n_lo + 32) : a.ntok;
+  for (int e = tid; e < (n_hi - n_lo) * 64; e += 256) {
+    const int nn = n_lo + (e >> 6), r = e & 63;
     if (row_base + r < a.d_out) a.y[(size_t)nn * a.d_out + row_base + r] = out[nn][r];
   }
 }
@@ -836,7 +839,9 @@ int launch_tile(const owq_layer_info_t &g, void *blob, void *scratch, uint64_t s
     fa.y = yp + (size_t)t0 * g.d_out;
     fa.ntok = ntok;
     fa.task_id = tasks.task_id ? tasks.task_id + t0 : nullptr;
-    hipLaunchKernelGGL(owq_tile_finish, dim3((unsigned)(n_rg * waves), 1, 1), dim3(256, 1, 1), 0, st, fa);
+    // few rows: one workgroup per (64 rows, token tile), so that the launch fills more of the chip
+    const unsigned per_tile = (ntok > 32 && n_rg * waves <= 384) ? 2u : 1u;
+    hipLaunchKernelGGL(owq_tile_finish, dim3((unsigned)(n_rg * waves), per_tile, 1), dim3(256, 1, 1), 0, st, fa);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
