@@ -83,7 +83,7 @@ typedef struct {
 
 /*
  * Two packed layouts hold the same content.  OWQ_LAYOUT_GEMV is built for single tokens
- * (one lane streams 128 columns of one row; a batch is one pass over the weights per token).
+ * (one lane streams 128 columns of one row; a batch is one pass over the weights per two tokens, where the shape allows, else per token).
  * OWQ_LAYOUT_TILE is built for batches: 32 rows by 256 columns per tile, unpacked straight
  * into matrix-core operands, one pass over the weights per 64 tokens (half the matrix work
  * for 32 tokens or fewer).  Either layout accepts any batch and gives the same result up to
